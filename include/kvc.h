@@ -1,0 +1,211 @@
+/*
+ * kvc.h -- C ABI of libkvc: the pack / restore hot path of video-codec based
+ * remote KV-cache reuse (KVCodec, arXiv 2602.09725) on one AMD MI355X (gfx950).
+ *
+ * What the library computes
+ * -------------------------
+ * Compress side (Sec. 3.2 "Codec-friendly KV Compression", Sec. 4 item (1)):
+ * the KV cache of an inference engine, shape [token, layer, head_num, head_dim]
+ * (Sec. 3.2, first paragraph), is quantized to 8-bit integers and laid out as
+ * video frames [frame, height, width, 3]:
+ *   - inter-frame layout (Sec. 3.2.1, steps 1-3): three consecutive layers
+ *     become the three colour planes of a frame; the T token tensors of a chunk
+ *     are split into groups of F adjacent tokens, and the F tensors of a group
+ *     occupy the same tile position in F consecutive frames;
+ *   - intra-frame layout (Sec. 3.2.2, rules i-iii and the tiles (8,512),
+ *     (8,128), (16,64) found there): the head_num*head_dim vector of one token
+ *     and layer is re-tiled row-major into a (tile_h, tile_w) block with no
+ *     permutation of heads or of elements inside a head.
+ * Fetch side (Sec. 3.3.2 "Frame-wise KV tensor restoration", Sec. 4 item (2)):
+ * decoded frames are mapped back to KV tensors, dequantized and written into the
+ * preallocated slots of the engine's paged memory.  The H.265 encoder / decoder
+ * between the two sides is lossless (Sec. 4 item (1)), so frames out == frames
+ * in, and it is not part of this library: frames are an opaque byte boundary.
+ * The pipelined fetcher follows the transmission/decoding overlap of Sec. 3.3.2
+ * ("Adaptive resolution KV fetching", first paragraph) with host->device copies
+ * of frame buffers standing in for the transmission stage.
+ *
+ * Notation: L layers, H KV heads, D head_dim, C = H*D, T = chunk_tokens,
+ * (th, tw) = tile with th*tw == C, (TX, TY) = tile grid of a frame,
+ * G = TX*TY tile positions, F = ceil(T / G) frames per layer group,
+ * LG = ceil(L / 3) layer groups, W = TX*tw, Hp = TY*th.
+ *
+ * Quantizer (the paper only says "quantized to integers", Sec. 4 item (1); the
+ * 8-bit asymmetric affine form is this library's definition), all in fp32:
+ *   group  : KVC_Q_PER_CHANNEL -> one (chunk, kind, layer, head, dim) over the
+ *            chunk's valid tokens; KVC_Q_PER_TOKEN -> one (kind, layer, token,
+ *            head) over the D elements of the head
+ *   mn     = min + 0.0f (so -0.0 becomes +0.0), range = max - mn
+ *   scale  = range / 255, inv = 255 / range (both correctly rounded; 0 if range==0)
+ *   code   = clamp(rint((x - mn) * inv), 0, 255)   rint = round half to even
+ *   x_hat  = fma(code, scale, mn), rounded to nearest even into fp16 / bf16
+ *
+ * Byte layouts
+ * ------------
+ * frames : [chunk][kind(K=0,V=1)][LG][F][3][Hp][W] uint8, planar.  The byte of
+ *          element (kind, l, t, h, d), t local to the chunk, sits at
+ *            e = h*D + d ; r = e / tw ; cc = e % tw
+ *            f = t % F   ; g = t / F  ; ty = g / TX ; tx = g % TX
+ *            y = ty*th + r ; x = tx*tw + cc ; lg = l / 3 ; pl = l % 3
+ *          Every byte no valid element maps to (planes of layers >= L, tiles of
+ *          tokens beyond the chunk's valid count) is 0.
+ * meta   : per chunk [K block][V block] of {scale, mn} fp32 pairs;
+ *          per-channel block = [L][H][D] pairs, per-token block = [L][T][H]
+ *          pairs (pairs of tokens beyond the valid count are {0, 0}).
+ * Multi-chunk buffers are arrays of fixed-stride chunk sections:
+ * frames = n_chunks * frame_bytes, meta = n_chunks * meta_bytes, with
+ * n_chunks = ceil(n_tokens / T); only the last chunk may be short.
+ * blob   : one chunk as shipped to a fetcher: its frame section, zero padding up
+ *          to kvc_blob_meta_offset() (frame_bytes rounded up to 256), then its
+ *          meta section.
+ *
+ * Conventions
+ * -----------
+ * Pointers marked DEVICE must be device memory valid on the current HIP device;
+ * pointers marked HOST are ordinary host memory (PINNED where stated).  The
+ * caller owns every buffer; the library allocates no device memory and keeps no
+ * reference after a call returns.  Data calls enqueue work on the given stream
+ * (a hipStream_t passed as void*, NULL = the default stream) and return without
+ * synchronizing unless stated.  Every host-checkable fault returns an error
+ * code before anything is enqueued; nothing throws across the ABI.  Calls are
+ * thread-safe for distinct streams.  Inputs must be finite; for each group
+ * either max == min or (max - min) >= 2^-100.
+ * Required alignment: kv / cache base pointers and strides 16 bytes, frames
+ * 16 bytes, meta 8 bytes; otherwise KVC_ERR_INVALID_ARG.
+ */
+#ifndef KVC_H
+#define KVC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVC_ABI_VERSION 1u
+
+typedef enum {
+  KVC_OK = 0,
+  KVC_ERR_INVALID_ARG = 1,      /* null pointer, inconsistent layout, bad alignment, bad range */
+  KVC_ERR_UNSUPPORTED = 2,      /* well-formed request outside what the kernels cover        */
+  KVC_ERR_BUFFER_TOO_SMALL = 3, /* a capacity argument is smaller than the call needs         */
+  KVC_ERR_RUNTIME = 4           /* a HIP runtime call failed                                   */
+} kvc_status;
+
+typedef enum { KVC_F16 = 0, KVC_BF16 = 1 } kvc_dtype;
+typedef enum { KVC_Q_PER_CHANNEL = 0, KVC_Q_PER_TOKEN = 1 } kvc_qmode;
+
+/* Geometry of one packed stream.  Read on the host during a call only. */
+typedef struct {
+  uint32_t struct_size;  /* sizeof(kvc_layout) as the caller compiled it           */
+  uint32_t abi_version;  /* KVC_ABI_VERSION                                        */
+  int32_t num_layers;    /* L >= 1                                                 */
+  int32_t num_kv_heads;  /* H >= 1                                                 */
+  int32_t head_dim;      /* D >= 1; a multiple of 8, else KVC_ERR_UNSUPPORTED      */
+  int32_t dtype;         /* kvc_dtype of the KV tensors                            */
+  int32_t chunk_tokens;  /* T >= 1 tokens per chunk (Sec. 4 item (1): chunking)    */
+  int32_t tile_h;        /* th, tile_h*tile_w == H*D (Sec. 3.2.2)                  */
+  int32_t tile_w;        /* tw; a multiple of 8, else KVC_ERR_UNSUPPORTED          */
+  int32_t tiles_x;       /* TX: tiles per frame row; sets the frame resolution     */
+  int32_t tiles_y;       /* TY: tiles per frame column (Sec. 3.2.1 observation iii)*/
+  int32_t k_mode;        /* kvc_qmode for K (default per channel)                  */
+  int32_t v_mode;        /* kvc_qmode for V (default per token)                    */
+} kvc_layout;
+
+/* Strides of a contiguous-style KV tensor [L][2][tokens][H][D], in ELEMENTS.
+ * The innermost [H][D] block of one token is contiguous.  Each stride must be a
+ * multiple of 8 elements. */
+typedef struct {
+  int64_t layer_stride;
+  int64_t kv_stride;
+  int64_t token_stride;
+} kvc_strides;
+
+/* One chunk blob in PINNED HOST memory (see "blob" above). */
+typedef struct {
+  const void* host_blob;
+  size_t bytes;     /* >= kvc_blob_meta_offset + meta_bytes */
+  int64_t n_tokens; /* valid tokens of this chunk, 1..T      */
+} kvc_host_chunk;
+
+/* Checks a layout for internal consistency (sizes positive, tile product,
+ * struct_size / abi_version).  HOST pointer. */
+kvc_status kvc_layout_validate(const kvc_layout* layout);
+
+/* Sizes of one chunk section.  Any output pointer may be NULL.
+ * frame_bytes = 2*LG*F*3*Hp*W ; meta_bytes = 8 * (pairs of K block + V block);
+ * frames_per_group = F (Sec. 3.2.1 step 2). */
+kvc_status kvc_chunk_sizes(const kvc_layout* layout, size_t* frame_bytes, size_t* meta_bytes,
+                           int32_t* frames_per_group);
+
+/* Offset of the meta section inside a chunk blob; blob size = offset + meta_bytes. */
+size_t kvc_blob_meta_offset(const kvc_layout* layout);
+
+/* Compress side: quantize + codec-friendly layout (Sec. 3.2.1 steps 1-3,
+ * Sec. 3.2.2, Sec. 4 item (1)).
+ *   kv        DEVICE in : [L][2][n_tokens][H][D] fp16|bf16 addressed by `strides`
+ *   n_tokens  tokens to pack (0 is allowed and does nothing)
+ *   frames    DEVICE out: ceil(n_tokens/T) chunk sections, every byte written
+ *   meta      DEVICE out: ceil(n_tokens/T) chunk sections, every byte written
+ *   *_cap     capacities in bytes; too small -> KVC_ERR_BUFFER_TOO_SMALL */
+kvc_status kvc_pack(const kvc_layout* layout, const void* kv, kvc_strides strides, int64_t n_tokens,
+                    uint8_t* frames, size_t frames_cap, void* meta, size_t meta_cap, void* stream);
+
+/* Fetch side into a contiguous tensor (Sec. 3.3.2 frame-wise restoration:
+ * unpack + dequantize).
+ *   frames, meta  DEVICE in : chunk sections as written by kvc_pack
+ *   kv_out        DEVICE out: [L][2][n_tokens][H][D] addressed by `strides`;
+ *                 only the n_tokens valid tokens are written. */
+kvc_status kvc_restore(const kvc_layout* layout, const uint8_t* frames, const void* meta,
+                       int64_t n_tokens, void* kv_out, kvc_strides strides, void* stream);
+
+/* Fetch side into the engine's paged memory (Sec. 3.3.2: "filled into the
+ * preallocated slots in the paged memory"; Sec. 4 item (2): the sparse
+ * frame-to-paged-memory transfer operator).
+ *   frames, meta   DEVICE in : sections of the chunks that hold sequence
+ *                  positions [first_token, first_token + n_tokens)
+ *   first_token    absolute position of token 0 of `frames`; multiple of T
+ *   d_layer_cache  DEVICE in : array of L DEVICE pointers, layer l's cache is
+ *                  [2][num_blocks][block_size][H][D] of the layout's dtype
+ *   d_block_table  DEVICE in : int32[table_len], logical block -> physical
+ *                  block; token p goes to block d_block_table[p / block_size],
+ *                  slot p % block_size; needs
+ *                  table_len*block_size >= first_token + n_tokens
+ *   d_err          DEVICE in/out, may be NULL: a physical id outside
+ *                  [0, num_blocks) cannot be seen from the host; the kernel
+ *                  skips the writes of that block and ORs 1 into *d_err. */
+kvc_status kvc_restore_paged(const kvc_layout* layout, const uint8_t* frames, const void* meta,
+                             int64_t first_token, int64_t n_tokens, void* const* d_layer_cache,
+                             int64_t num_blocks, int32_t block_size, const int32_t* d_block_table,
+                             int64_t table_len, uint32_t* d_err, void* stream);
+
+/* Pipelined fetcher (Sec. 3.3.2: transmission overlapped with decoding, the
+ * restoration riding along; Sec. 3.3.2 "bitstream buffer in host memory").
+ * Chunk i (holding sequence positions i*T ...) is copied from its pinned HOST
+ * blob to staging slot i % n_staging on `copy_stream`, then restored into the
+ * paged cache on `compute_stream`; a slot is reused only after the restore that
+ * read it has finished.  Every chunk but the last must hold T tokens.
+ *   chunks            HOST array of n_chunks descriptors (blobs PINNED HOST)
+ *   d_staging         HOST array of n_staging DEVICE buffers, each >= blob size
+ *   staging_bytes     capacity of each staging buffer
+ *   n_staging         >= 2
+ *   copy_stream, compute_stream : two distinct non-NULL hipStream_t
+ *   fetch_to_ready_ms HOST out, may be NULL.  If non-NULL the call blocks until
+ *                     the last restore has finished and stores the time from
+ *                     the first copy being enqueued to that moment; if NULL the
+ *                     call returns after enqueueing and the caller synchronizes
+ *                     compute_stream. */
+kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* chunks, int32_t n_chunks,
+                              void* const* d_staging, size_t staging_bytes, int32_t n_staging,
+                              void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
+                              const int32_t* d_block_table, int64_t table_len, uint32_t* d_err,
+                              void* copy_stream, void* compute_stream, float* fetch_to_ready_ms);
+
+/* Static, never-freed description of a status code. */
+const char* kvc_status_str(kvc_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVC_H */

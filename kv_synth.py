@@ -1,0 +1,106 @@
+"""Seeded synthetic KV tensors and the workload shapes they come in.
+
+This module only makes inputs: it holds none of the method's arithmetic (no
+quantizer, no layout) and is the one piece shared by the GPU tests, the CPU
+oracle tests and the benchmark.
+
+Value recipe (stands in for KV caches of real long-context prompts, which need
+trained weights and datasets): for every channel (kind, layer, head, dim) a
+standard deviation sigma_c is drawn log-uniformly from [0.1, 4]; with
+probability 0.01 the channel is an outlier and sigma_c is multiplied by 10;
+values are i.i.d. N(0, sigma_c) over tokens, rounded to fp16 / bf16.
+"""
+import math
+from dataclasses import dataclass
+
+import torch
+
+BASE_SEED = 2602_09725
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    index: int          # position in the list of benchmark configurations
+    L: int
+    H: int
+    D: int
+    n_tokens: int
+    dtype: str          # "f16" | "bf16"
+    T: int = 2048       # tokens per chunk
+    th: int = 8         # tile (Sec. 3.2.2: (8,128) is the tile found for H=8, D=128)
+    tw: int = 128
+    TX: int = 8         # tile grid: 8 x 64 positions -> F = 4 frames per group
+    TY: int = 64
+    block_size: int = 16
+    paged: bool = False
+
+    @property
+    def C(self):
+        return self.H * self.D
+
+    @property
+    def n_chunks(self):
+        return (self.n_tokens + self.T - 1) // self.T
+
+    @property
+    def n_logical_blocks(self):
+        return (self.n_tokens + self.block_size - 1) // self.block_size
+
+    @property
+    def torch_dtype(self):
+        return torch.float16 if self.dtype == "f16" else torch.bfloat16
+
+    @property
+    def seed(self):
+        return BASE_SEED + self.index
+
+
+WORKLOADS = {
+    "tiny": Workload("tiny", 0, L=2, H=8, D=128, n_tokens=2048, dtype="f16"),
+    "llama3_8b_8k": Workload("llama3_8b_8k", 1, L=32, H=8, D=128, n_tokens=8192, dtype="f16"),
+    "llama3_8b_32k_paged": Workload("llama3_8b_32k_paged", 2, L=32, H=8, D=128, n_tokens=32768, dtype="f16", paged=True),
+    "yi34b_80k_paged": Workload("yi34b_80k_paged", 3, L=60, H=8, D=128, n_tokens=80000, dtype="bf16", paged=True),
+    "llama3_8b_32k_pipeline": Workload("llama3_8b_32k_pipeline", 4, L=32, H=8, D=128, n_tokens=32768, dtype="f16", paged=True),
+}
+
+
+def channel_sigmas(L, C, gen, device):
+    """sigma for every (layer, kind, channel): log-uniform in [0.1, 4], 1 % of channels x10."""
+    u = torch.rand((L, 2, C), generator=gen, device=device, dtype=torch.float32)
+    sigma = torch.exp(math.log(0.1) + u * (math.log(4.0) - math.log(0.1)))
+    outlier = torch.rand((L, 2, C), generator=gen, device=device, dtype=torch.float32) < 0.01
+    return torch.where(outlier, sigma * 10.0, sigma)
+
+
+def make_kv(L, H, D, n_tokens, dtype, seed, device="cpu"):
+    """Returns a contiguous [L][2][n_tokens][H][D] tensor of the given torch dtype."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    C = H * D
+    sigma = channel_sigmas(L, C, gen, device)
+    kv = torch.empty((L, 2, n_tokens, H, D), dtype=dtype, device=device)
+    for l in range(L):  # one layer at a time bounds the fp32 temporary
+        z = torch.randn((2, n_tokens, C), generator=gen, device=device, dtype=torch.float32)
+        kv[l] = (z * sigma[l].unsqueeze(1)).to(dtype).view(2, n_tokens, H, D)
+    return kv
+
+
+def make_workload_kv(w: Workload, device="cpu", n_tokens=None):
+    return make_kv(w.L, w.H, w.D, w.n_tokens if n_tokens is None else n_tokens, w.torch_dtype, w.seed, device)
+
+
+def make_block_table(n_logical, num_blocks, seed, device="cpu"):
+    """Seeded random injection logical block -> physical block (a permutation when
+    num_blocks == n_logical, else a random subset of the physical blocks)."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    perm = torch.randperm(num_blocks, generator=gen)[:n_logical].to(torch.int32)
+    return perm.to(device)
+
+
+def to_u16(t: torch.Tensor):
+    """numpy uint16 view of a CPU fp16 / bf16 tensor (bit patterns)."""
+    import numpy as np
+
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
