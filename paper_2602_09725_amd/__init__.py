@@ -1,0 +1,10 @@
+"""MI355X-native pack / restore of KV caches as video-frame planes (KVCodec hot path).
+
+Thin binding over libkvc.so (see include/kvc.h): argument marshalling only,
+every step runs in the HIP kernels.  There is no CPU fallback: importing works
+anywhere, calling needs the built library and a gfx950 GPU.
+"""
+from .kvc import (  # noqa: F401
+    KVC_BF16, KVC_F16, KVC_Q_PER_CHANNEL, KVC_Q_PER_TOKEN, KvcError, Layout, blob_meta_offset, chunk_sizes,
+    kvc_fetch_pipeline, kvc_pack, kvc_restore, kvc_restore_paged, layout_validate, lib_path, load, status_str,
+)

@@ -1,0 +1,314 @@
+// Host layer of libkvc: argument validation, derived geometry, the C ABI of
+// include/kvc.h and the two-stream fetch pipeline.
+#include <hip/hip_runtime.h>
+
+#include <limits.h>
+
+#include "kvc_launch.h"
+
+namespace kvc {
+
+namespace {
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+kvc_status check_layout(const kvc_layout* lo) {
+  if (!lo) return KVC_ERR_INVALID_ARG;
+  if (lo->struct_size != sizeof(kvc_layout) || lo->abi_version != KVC_ABI_VERSION) return KVC_ERR_INVALID_ARG;
+  if (lo->num_layers < 1 || lo->num_kv_heads < 1 || lo->head_dim < 1 || lo->chunk_tokens < 1) return KVC_ERR_INVALID_ARG;
+  if (lo->tile_h < 1 || lo->tile_w < 1 || lo->tiles_x < 1 || lo->tiles_y < 1) return KVC_ERR_INVALID_ARG;
+  if ((int64_t)lo->tile_h * lo->tile_w != (int64_t)lo->num_kv_heads * lo->head_dim) return KVC_ERR_INVALID_ARG;
+  if (lo->dtype != KVC_F16 && lo->dtype != KVC_BF16) return KVC_ERR_INVALID_ARG;
+  if (lo->k_mode != KVC_Q_PER_CHANNEL && lo->k_mode != KVC_Q_PER_TOKEN) return KVC_ERR_INVALID_ARG;
+  if (lo->v_mode != KVC_Q_PER_CHANNEL && lo->v_mode != KVC_Q_PER_TOKEN) return KVC_ERR_INVALID_ARG;
+  // sizes the 32-bit in-plane arithmetic of the kernels can hold
+  const int64_t C = (int64_t)lo->num_kv_heads * lo->head_dim;
+  const int64_t G = (int64_t)lo->tiles_x * lo->tiles_y;
+  const int64_t F = ceil_div(lo->chunk_tokens, G);
+  if (C > (1 << 20) || G > (1 << 28) || F * G >= (1ll << 30) || G * C >= (1ll << 31)) return KVC_ERR_UNSUPPORTED;
+  if ((int64_t)lo->num_layers > (1 << 20) || (int64_t)lo->chunk_tokens * lo->num_kv_heads >= (1ll << 31))
+    return KVC_ERR_UNSUPPORTED;
+  return KVC_OK;
+}
+
+hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+kvc_status check_strides(const kvc_strides& s) {
+  if (s.layer_stride < 0 || s.kv_stride < 0 || s.token_stride < 0) return KVC_ERR_INVALID_ARG;
+  if ((s.layer_stride | s.kv_stride | s.token_stride) & 7) return KVC_ERR_INVALID_ARG;
+  return KVC_OK;
+}
+
+}  // namespace
+
+kvc_status make_geo(const kvc_layout* lo, Geo* g) {
+  const kvc_status st = check_layout(lo);
+  if (st != KVC_OK) return st;
+  if (lo->head_dim % 8 != 0 || lo->tile_w % 8 != 0) return KVC_ERR_UNSUPPORTED;
+  g->L = lo->num_layers;
+  g->H = lo->num_kv_heads;
+  g->D = lo->head_dim;
+  g->C = g->H * g->D;
+  g->T = lo->chunk_tokens;
+  g->th = lo->tile_h;
+  g->tw = lo->tile_w;
+  g->TX = lo->tiles_x;
+  g->TY = lo->tiles_y;
+  g->G = g->TX * g->TY;
+  g->F = (int32_t)ceil_div(g->T, g->G);
+  g->FG = g->F * g->G;
+  g->LG = (int32_t)ceil_div(g->L, 3);
+  g->W = g->TX * g->tw;
+  g->Hp = g->TY * g->th;
+  g->apt = g->C / 8;
+  g->dtype = lo->dtype;
+  g->mode[0] = lo->k_mode;
+  g->mode[1] = lo->v_mode;
+  g->plane = (int64_t)g->Hp * g->W;
+  g->frame_bytes = 2ll * g->LG * g->F * 3 * g->plane;
+  int64_t pairs[2];
+  for (int k = 0; k < 2; ++k)
+    pairs[k] = g->mode[k] == KVC_Q_PER_CHANNEL ? (int64_t)g->L * g->C : (int64_t)g->L * g->T * g->H;
+  g->meta_off[0] = 0;
+  g->meta_off[1] = 2 * pairs[0];
+  g->meta_floats = 2 * (pairs[0] + pairs[1]);
+  g->dF = make_fastdiv((uint32_t)g->F);
+  g->dTX = make_fastdiv((uint32_t)g->TX);
+  g->dtw = make_fastdiv((uint32_t)g->tw);
+  g->dD = make_fastdiv((uint32_t)g->D);
+  return KVC_OK;
+}
+
+}  // namespace kvc
+
+using namespace kvc;
+
+extern "C" {
+
+const char* kvc_status_str(kvc_status status) {
+  switch (status) {
+    case KVC_OK: return "ok";
+    case KVC_ERR_INVALID_ARG: return "invalid argument";
+    case KVC_ERR_UNSUPPORTED: return "unsupported layout or size";
+    case KVC_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+    case KVC_ERR_RUNTIME: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+kvc_status kvc_layout_validate(const kvc_layout* layout) { return check_layout(layout); }
+
+kvc_status kvc_chunk_sizes(const kvc_layout* layout, size_t* frame_bytes, size_t* meta_bytes,
+                           int32_t* frames_per_group) {
+  const kvc_status st = check_layout(layout);
+  if (st != KVC_OK) return st;
+  const int64_t C = (int64_t)layout->num_kv_heads * layout->head_dim;
+  const int64_t G = (int64_t)layout->tiles_x * layout->tiles_y;
+  const int64_t F = ceil_div(layout->chunk_tokens, G);
+  const int64_t LG = ceil_div(layout->num_layers, 3);
+  int64_t pairs = 0;
+  const int modes[2] = {layout->k_mode, layout->v_mode};
+  for (int k = 0; k < 2; ++k)
+    pairs += modes[k] == KVC_Q_PER_CHANNEL ? (int64_t)layout->num_layers * C
+                                           : (int64_t)layout->num_layers * layout->chunk_tokens * layout->num_kv_heads;
+  if (frame_bytes) *frame_bytes = (size_t)(2 * LG * F * 3 * G * C);
+  if (meta_bytes) *meta_bytes = (size_t)(8 * pairs);
+  if (frames_per_group) *frames_per_group = (int32_t)F;
+  return KVC_OK;
+}
+
+size_t kvc_blob_meta_offset(const kvc_layout* layout) {
+  size_t fb = 0;
+  if (kvc_chunk_sizes(layout, &fb, nullptr, nullptr) != KVC_OK) return 0;
+  return (fb + 255) & ~(size_t)255;
+}
+
+kvc_status kvc_pack(const kvc_layout* layout, const void* kv, kvc_strides strides, int64_t n_tokens, uint8_t* frames,
+                    size_t frames_cap, void* meta, size_t meta_cap, void* stream) {
+  PackParams p{};
+  kvc_status st = make_geo(layout, &p.g);
+  if (st != KVC_OK) return st;
+  if (n_tokens < 0 || n_tokens >= (1ll << 31)) return KVC_ERR_INVALID_ARG;
+  if (n_tokens == 0) return KVC_OK;
+  if (!kv || !frames || !meta) return KVC_ERR_INVALID_ARG;
+  if ((st = check_strides(strides)) != KVC_OK) return st;
+  if (!aligned(kv, 16) || !aligned(frames, 16) || !aligned(meta, 8)) return KVC_ERR_INVALID_ARG;
+  if (strides.token_stride < p.g.C) return KVC_ERR_INVALID_ARG;
+  const int64_t n_chunks = ceil_div(n_tokens, p.g.T);
+  if ((uint64_t)(n_chunks * p.g.frame_bytes) > frames_cap) return KVC_ERR_BUFFER_TOO_SMALL;
+  if ((uint64_t)(n_chunks * p.g.meta_floats * 4) > meta_cap) return KVC_ERR_BUFFER_TOO_SMALL;
+  p.kv = static_cast<const uint16_t*>(kv);
+  p.ls = strides.layer_stride;
+  p.ks = strides.kv_stride;
+  p.ts = strides.token_stride;
+  p.n_tokens = n_tokens;
+  p.frames = frames;
+  p.meta = static_cast<float*>(meta);
+  return launch_pack(p, as_stream(stream));
+}
+
+kvc_status kvc_restore(const kvc_layout* layout, const uint8_t* frames, const void* meta, int64_t n_tokens,
+                       void* kv_out, kvc_strides strides, void* stream) {
+  RestoreParams p{};
+  kvc_status st = make_geo(layout, &p.g);
+  if (st != KVC_OK) return st;
+  if (n_tokens < 0 || n_tokens >= (1ll << 31)) return KVC_ERR_INVALID_ARG;
+  if (n_tokens == 0) return KVC_OK;
+  if (!kv_out || !frames || !meta) return KVC_ERR_INVALID_ARG;
+  if ((st = check_strides(strides)) != KVC_OK) return st;
+  if (!aligned(kv_out, 16) || !aligned(frames, 16) || !aligned(meta, 8)) return KVC_ERR_INVALID_ARG;
+  if (strides.token_stride < p.g.C) return KVC_ERR_INVALID_ARG;
+  p.frames = frames;
+  p.meta = static_cast<const float*>(meta);
+  p.n_tokens = n_tokens;
+  p.out = static_cast<uint16_t*>(kv_out);
+  p.ls = strides.layer_stride;
+  p.ks = strides.kv_stride;
+  p.ts = strides.token_stride;
+  p.dbs = make_fastdiv(1);
+  return launch_restore(p, false, as_stream(stream));
+}
+
+namespace {
+
+// Argument checks shared by kvc_restore_paged and kvc_fetch_pipeline.
+kvc_status fill_paged(RestoreParams& p, int64_t first_token, int64_t n_tokens, void* const* d_layer_cache,
+                      int64_t num_blocks, int32_t block_size, const int32_t* d_block_table, int64_t table_len,
+                      uint32_t* d_err) {
+  if (n_tokens < 0 || first_token < 0 || first_token + n_tokens >= (1ll << 31)) return KVC_ERR_INVALID_ARG;
+  if (first_token % p.g.T != 0) return KVC_ERR_INVALID_ARG;
+  if (num_blocks < 1 || num_blocks >= (1ll << 31) || block_size < 1 || table_len < 0) return KVC_ERR_INVALID_ARG;
+  if (!d_layer_cache || !d_block_table) return KVC_ERR_INVALID_ARG;
+  if (table_len * block_size < first_token + n_tokens) return KVC_ERR_INVALID_ARG;
+  if (d_err && !aligned(d_err, 4)) return KVC_ERR_INVALID_ARG;
+  p.layer_cache = d_layer_cache;
+  p.table = d_block_table;
+  p.num_blocks = num_blocks;
+  p.dbs = make_fastdiv((uint32_t)block_size);
+  p.first_token = first_token;
+  p.err = d_err;
+  p.n_tokens = n_tokens;
+  return KVC_OK;
+}
+
+}  // namespace
+
+kvc_status kvc_restore_paged(const kvc_layout* layout, const uint8_t* frames, const void* meta, int64_t first_token,
+                             int64_t n_tokens, void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
+                             const int32_t* d_block_table, int64_t table_len, uint32_t* d_err, void* stream) {
+  RestoreParams p{};
+  kvc_status st = make_geo(layout, &p.g);
+  if (st != KVC_OK) return st;
+  if ((st = fill_paged(p, first_token, n_tokens, d_layer_cache, num_blocks, block_size, d_block_table, table_len,
+                       d_err)) != KVC_OK)
+    return st;
+  if (n_tokens == 0) return KVC_OK;
+  if (!frames || !meta) return KVC_ERR_INVALID_ARG;
+  if (!aligned(frames, 16) || !aligned(meta, 8)) return KVC_ERR_INVALID_ARG;
+  p.frames = frames;
+  p.meta = static_cast<const float*>(meta);
+  return launch_restore(p, true, as_stream(stream));
+}
+
+kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* chunks, int32_t n_chunks,
+                              void* const* d_staging, size_t staging_bytes, int32_t n_staging,
+                              void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
+                              const int32_t* d_block_table, int64_t table_len, uint32_t* d_err, void* copy_stream,
+                              void* compute_stream, float* fetch_to_ready_ms) {
+  RestoreParams base{};
+  kvc_status st = make_geo(layout, &base.g);
+  if (st != KVC_OK) return st;
+  if (n_chunks < 0 || n_chunks > 4096) return KVC_ERR_INVALID_ARG;
+  if (n_chunks == 0) {
+    if (fetch_to_ready_ms) *fetch_to_ready_ms = 0.f;
+    return KVC_OK;
+  }
+  if (!chunks || !d_staging || n_staging < 2 || n_staging > 64) return KVC_ERR_INVALID_ARG;
+  if (!copy_stream || !compute_stream || copy_stream == compute_stream) return KVC_ERR_INVALID_ARG;
+  const size_t meta_off = kvc_blob_meta_offset(layout);
+  const size_t blob_bytes = meta_off + (size_t)base.g.meta_floats * 4;
+  if (staging_bytes < blob_bytes) return KVC_ERR_BUFFER_TOO_SMALL;
+  int64_t total = 0;
+  for (int i = 0; i < n_chunks; ++i) {
+    if (!chunks[i].host_blob) return KVC_ERR_INVALID_ARG;
+    if (chunks[i].bytes < blob_bytes) return KVC_ERR_BUFFER_TOO_SMALL;
+    if (chunks[i].n_tokens < 1 || chunks[i].n_tokens > base.g.T) return KVC_ERR_INVALID_ARG;
+    if (i + 1 < n_chunks && chunks[i].n_tokens != base.g.T) return KVC_ERR_INVALID_ARG;
+    total += chunks[i].n_tokens;
+  }
+  for (int s = 0; s < n_staging; ++s)
+    if (!d_staging[s] || !aligned(d_staging[s], 256)) return KVC_ERR_INVALID_ARG;
+  // whole-range check of the paged destination before anything is enqueued
+  if ((st = fill_paged(base, 0, total, d_layer_cache, num_blocks, block_size, d_block_table, table_len, d_err)) != KVC_OK)
+    return st;
+
+  hipStream_t cs = as_stream(copy_stream), xs = as_stream(compute_stream);
+  // One "copied" event per chunk and one "slot free" event per staging slot.
+  hipEvent_t copied[64], freed[64], t_begin = nullptr, t_end = nullptr;
+  bool ok = true;
+  int n_ev = 0;
+  for (; n_ev < n_staging && ok; ++n_ev) {
+    ok = hipEventCreateWithFlags(&copied[n_ev], hipEventDisableTiming) == hipSuccess;
+    if (ok) {
+      ok = hipEventCreateWithFlags(&freed[n_ev], hipEventDisableTiming) == hipSuccess;
+      if (!ok) (void)hipEventDestroy(copied[n_ev]);
+    }
+    if (!ok) break;
+  }
+  if (ok && fetch_to_ready_ms) {
+    ok = hipEventCreate(&t_begin) == hipSuccess && hipEventCreate(&t_end) == hipSuccess;
+  }
+  kvc_status result = ok ? KVC_OK : KVC_ERR_RUNTIME;
+
+  if (ok) {
+    if (t_begin) ok = hipEventRecord(t_begin, cs) == hipSuccess;
+    for (int i = 0; i < n_chunks && ok; ++i) {
+      const int s = i % n_staging;
+      // the copy into slot s must wait for the restore that last read it
+      if (i >= n_staging) ok = hipStreamWaitEvent(cs, freed[s], 0) == hipSuccess;
+      if (ok) ok = hipMemcpyAsync(d_staging[s], chunks[i].host_blob, blob_bytes, hipMemcpyHostToDevice, cs) == hipSuccess;
+      if (ok) ok = hipEventRecord(copied[s], cs) == hipSuccess;
+      if (ok) ok = hipStreamWaitEvent(xs, copied[s], 0) == hipSuccess;
+      if (!ok) break;
+      RestoreParams p = base;
+      p.frames = static_cast<const uint8_t*>(d_staging[s]);
+      p.meta = reinterpret_cast<const float*>(static_cast<const uint8_t*>(d_staging[s]) + meta_off);
+      p.first_token = (int64_t)i * base.g.T;
+      p.n_tokens = chunks[i].n_tokens;
+      const kvc_status ls = launch_restore(p, true, xs);
+      if (ls != KVC_OK) {
+        result = ls;
+        ok = false;
+        break;
+      }
+      ok = hipEventRecord(freed[s], xs) == hipSuccess;
+    }
+    if (!ok && result == KVC_OK) result = KVC_ERR_RUNTIME;
+    if (t_end) {
+      // compute_stream is the later of the two by construction
+      if (hipEventRecord(t_end, xs) != hipSuccess || hipEventSynchronize(t_end) != hipSuccess) {
+        if (result == KVC_OK) result = KVC_ERR_RUNTIME;
+      } else if (result == KVC_OK) {
+        // t_begin sits on the copy stream, t_end on the compute stream
+        if (hipEventElapsedTime(fetch_to_ready_ms, t_begin, t_end) != hipSuccess) result = KVC_ERR_RUNTIME;
+      }
+    } else if (result != KVC_OK) {
+      // part of the work may be queued: let it drain before the events go away
+      (void)hipStreamSynchronize(cs);
+      (void)hipStreamSynchronize(xs);
+    }
+  }
+  // Destroying an event that is still pending is allowed: its resources are
+  // released once it completes, and the stream-side waits keep their ordering.
+  for (int i = 0; i < n_ev; ++i) {
+    (void)hipEventDestroy(copied[i]);
+    (void)hipEventDestroy(freed[i]);
+  }
+  if (t_begin) (void)hipEventDestroy(t_begin);
+  if (t_end) (void)hipEventDestroy(t_end);
+  return result;
+}
+
+}  // extern "C"

@@ -1,0 +1,63 @@
+// Kernel parameter blocks and the host-side launch functions of libkvc.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "kvc_common.h"
+
+namespace kvc {
+
+struct RestoreParams {
+  Geo g;
+  const uint8_t* frames;  // chunk sections
+  const float* meta;      // chunk sections
+  int64_t n_tokens;       // tokens held by `frames`
+  int32_t n_chunks;
+  int32_t tb;             // tokens per workgroup (0: library default)
+  int32_t tbc;            // token blocks per chunk
+  int32_t tpp;            // tokens per pass of a workgroup = threads / apt
+  uint32_t n_units;       // n_chunks * 2 * L * tbc workgroups with work
+  uint32_t units_per_xcd;
+  FastDiv dapt;
+  // contiguous destination
+  uint16_t* out;
+  int64_t ls, ks, ts;
+  // paged destination
+  void* const* layer_cache;
+  const int32_t* table;
+  int64_t num_blocks;
+  FastDiv dbs;            // block size
+  int64_t first_token;
+  uint32_t* err;
+};
+
+// Enqueues the fused unpack + dequantize + placement kernel.
+kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream);
+
+struct PackParams {
+  Geo g;
+  const uint16_t* kv;
+  int64_t ls, ks, ts;
+  int64_t n_tokens;
+  int32_t n_chunks;
+  uint8_t* frames;
+  float* meta;
+  // per-token kernel
+  int32_t tb, tbc, tpp;
+  FastDiv dapt;
+  // per-channel kernel
+  int32_t strip_atoms;    // atoms (8 channels each) per strip
+  int32_t n_strips;
+  int32_t rows;           // token rows per pass = threads / strip_atoms
+  // common
+  int32_t n_kinds;        // kinds handled by this launch
+  int32_t kinds[2];
+  uint32_t n_units;
+  uint32_t units_per_xcd;
+};
+
+// Enqueues statistics + quantize + layout for every kind, plus the zero fill of
+// unused planes and tile positions.
+kvc_status launch_pack(PackParams p, hipStream_t stream);
+
+}  // namespace kvc

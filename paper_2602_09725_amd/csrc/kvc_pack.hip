@@ -1,0 +1,373 @@
+// Pack kernels: group statistics, 8-bit quantization and the codec-friendly
+// layout (Sec. 3.2.1 steps 1-3, Sec. 3.2.2, Sec. 4 item (1)).
+//
+// Two kernels, one per quantization grouping:
+//  * per-token groups (one group = the D elements of one head of one token):
+//    statistics, quantization and the layout scatter fused in one pass.  A thread
+//    holds an atom of 8 consecutive elements; the D/8 lanes of a head reduce
+//    min/max with a cross-lane butterfly, so the input is read exactly once.
+//  * per-channel groups (one group = one channel over the valid tokens of a
+//    chunk): a workgroup owns a strip of channels of one (chunk, kind, layer),
+//    streams the strip once for the column min/max (registers + one LDS step
+//    across waves), then streams it again to quantize.  The strip (tokens x strip
+//    bytes) is sized so the second read is served from cache, not HBM.
+// Both kernels write every byte of their part of the frame section, zero for
+// tile positions without a token and for the planes of layers beyond L, so the
+// caller never has to clear the buffer.
+#include <hip/hip_runtime.h>
+
+#include "kvc_device.h"
+#include "kvc_launch.h"
+
+namespace kvc {
+
+#ifndef KVC_PACK_U
+#define KVC_PACK_U 4  // loads in flight per thread
+#endif
+
+namespace {
+
+struct GroupParams {
+  float scale, mn, inv;
+};
+
+// scale / min / reciprocal step of one group from its min and max (all fp32,
+// both divisions correctly rounded).
+__device__ __forceinline__ GroupParams group_params(float lo, float hi) {
+  GroupParams q;
+  q.mn = lo == 0.0f ? 0.0f : lo;  // -0.0 -> +0.0
+  const float range = hi - q.mn;
+  if (range == 0.0f) {
+    q.scale = 0.0f;
+    q.inv = 0.0f;
+  } else {
+    q.scale = range / 255.0f;
+    q.inv = 255.0f / range;
+  }
+  return q;
+}
+
+// code = clamp(rint((x - mn) * inv), 0, 255); subtraction and product are
+// separately rounded (no contraction is possible: there is no add after the mul).
+__device__ __forceinline__ uint32_t quantize(float x, float mn, float inv) {
+  const float pos = (x - mn) * inv;
+  float q = __builtin_rintf(pos);
+  q = __builtin_fminf(__builtin_fmaxf(q, 0.0f), 255.0f);
+  return (uint32_t)q;
+}
+
+template <int DT>
+__device__ __forceinline__ void widen_atom(const u32x4& v, float (&x)[8]) {
+  widen_pair<DT>(v.x, x[0], x[1]);
+  widen_pair<DT>(v.y, x[2], x[3]);
+  widen_pair<DT>(v.z, x[4], x[5]);
+  widen_pair<DT>(v.w, x[6], x[7]);
+}
+
+__device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  return a | (b << 8) | (c << 16) | (d << 24);
+}
+
+// Address of the 8 code bytes of atom (row r, column cc already folded into
+// fbase) of token position t inside the (chunk, kind, layer) plane sequence.
+__device__ __forceinline__ uint8_t* code_addr(const Geo& g, uint8_t* fbase, uint32_t t) {
+  uint32_t gi, f, ty, tx;
+  fd_divmod(g.dF, t, gi, f);      // Sec. 3.2.1 step 2: group and index inside the group
+  fd_divmod(g.dTX, gi, ty, tx);   // tile position of the group, raster order
+  return fbase + (int64_t)f * 3 * g.plane + ((int64_t)ty * g.th * g.W + tx * (uint32_t)g.tw);
+}
+
+// ------------------------------------------------------------ per-token groups
+
+template <int DT, bool UNIFORM>
+__global__ void __launch_bounds__(1024) pack_token_kernel(const PackParams p) {
+  constexpr int U = KVC_PACK_U;
+  const Geo& g = p.g;
+  const uint32_t unit = (blockIdx.x & 7u) * p.units_per_xcd + (blockIdx.x >> 3);
+  if (unit >= p.n_units) return;
+  uint32_t uu = unit;
+  const uint32_t tbi = uu % (uint32_t)p.tbc;
+  uu /= (uint32_t)p.tbc;
+  const uint32_t l3 = (uint32_t)(3 * g.LG);
+  const uint32_t l = uu % l3;
+  uu /= l3;
+  const uint32_t kind = (uint32_t)p.kinds[uu % (uint32_t)p.n_kinds];
+  const uint32_t c = uu / (uint32_t)p.n_kinds;
+
+  const uint32_t tid = threadIdx.x;
+  uint32_t tsub = fd_div(p.dapt, tid);
+  const uint32_t ca = tid - tsub * (uint32_t)g.apt;
+  if (UNIFORM) tsub = wave_uniform(tsub);
+  const uint32_t e = ca * 8u;
+  const uint32_t glanes = (uint32_t)g.D / 8u;  // lanes of one group: a power of two <= 64
+
+  const int64_t chunk_first = (int64_t)c * g.T;
+  const int64_t left = p.n_tokens - chunk_first;
+  int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
+  if (l >= (uint32_t)g.L) n = 0;  // plane of a layer that does not exist: all zero
+  const int32_t t0 = (int32_t)tbi * p.tb;
+  const int32_t t1 = t0 + p.tb < g.FG ? t0 + p.tb : g.FG;
+
+  uint32_t r, cc;
+  fd_divmod(g.dtw, e, r, cc);
+  const uint32_t lg = l / 3u, pl = l - lg * 3u;
+  uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane +
+                   (r * (uint32_t)g.W + cc);
+  const uint32_t h = fd_div(g.dD, e);
+  float* mrow = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.T * g.H + h);
+  const uint16_t* src = p.kv + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts + e;
+  const bool leader = (ca & (glanes - 1u)) == 0u;
+
+  const int32_t step = p.tpp;
+  for (int32_t tb0 = t0; tb0 < t1; tb0 += U * step) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int32_t t = tb0 + u * step + (int32_t)tsub;
+      v[u] = u32x4{0u, 0u, 0u, 0u};
+      if (t < n) v[u] = stream_load<u32x4>(src + (int64_t)t * p.ts);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int32_t t = tb0 + u * step + (int32_t)tsub;
+      if (t >= t1) continue;
+      uint8_t* dst = code_addr(g, fbase, (uint32_t)t);
+      if (t >= n) {  // no token here: zero codes, zero pair
+        stream_store<u32x2>(dst, u32x2{0u, 0u});
+        if (leader && t < g.T && l < (uint32_t)g.L) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{0.f, 0.f};
+        continue;
+      }
+      float x[8];
+      widen_atom<DT>(v[u], x);
+      float lo = x[0], hi = x[0];
+#pragma unroll
+      for (int i = 1; i < 8; ++i) {
+        lo = __builtin_fminf(lo, x[i]);
+        hi = __builtin_fmaxf(hi, x[i]);
+      }
+      for (uint32_t m = 1; m < glanes; m <<= 1) {  // butterfly over the lanes of the head
+        lo = __builtin_fminf(lo, __shfl_xor(lo, (int)m));
+        hi = __builtin_fmaxf(hi, __shfl_xor(hi, (int)m));
+      }
+      const GroupParams q = group_params(lo, hi);
+      u32x2 o;
+      o.x = pack4(quantize(x[0], q.mn, q.inv), quantize(x[1], q.mn, q.inv), quantize(x[2], q.mn, q.inv),
+                  quantize(x[3], q.mn, q.inv));
+      o.y = pack4(quantize(x[4], q.mn, q.inv), quantize(x[5], q.mn, q.inv), quantize(x[6], q.mn, q.inv),
+                  quantize(x[7], q.mn, q.inv));
+      stream_store<u32x2>(dst, o);
+      if (leader) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{q.scale, q.mn};
+    }
+  }
+}
+
+// ---------------------------------------------------------- per-channel groups
+
+constexpr int kStripThreads = 256;
+constexpr int kStripWaves = kStripThreads / 64;
+
+template <int DT>
+__global__ void __launch_bounds__(kStripThreads) pack_channel_kernel(const PackParams p) {
+  constexpr int U = KVC_PACK_U;
+  const Geo& g = p.g;
+  const uint32_t unit = (blockIdx.x & 7u) * p.units_per_xcd + (blockIdx.x >> 3);
+  if (unit >= p.n_units) return;
+  uint32_t uu = unit;
+  const uint32_t strip = uu % (uint32_t)p.n_strips;
+  uu /= (uint32_t)p.n_strips;
+  const uint32_t l3 = (uint32_t)(3 * g.LG);
+  const uint32_t l = uu % l3;
+  uu /= l3;
+  const uint32_t kind = (uint32_t)p.kinds[uu % (uint32_t)p.n_kinds];
+  const uint32_t c = uu / (uint32_t)p.n_kinds;
+
+  const uint32_t tid = threadIdx.x;
+  const uint32_t sa = (uint32_t)p.strip_atoms;  // power of two <= 64
+  const uint32_t a = tid & (sa - 1u);
+  const uint32_t row = tid / sa;
+  const uint32_t rows = (uint32_t)p.rows;
+  const uint32_t ca = strip * sa + a;
+  const bool active = ca < (uint32_t)g.apt;
+  const uint32_t e = (active ? ca : 0u) * 8u;  // idle lanes of a ragged last strip shadow atom 0 and never store
+
+  const int64_t chunk_first = (int64_t)c * g.T;
+  const int64_t left = p.n_tokens - chunk_first;
+  int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
+  if (l >= (uint32_t)g.L) n = 0;
+
+  uint32_t r, cc;
+  fd_divmod(g.dtw, e, r, cc);
+  const uint32_t lg = l / 3u, pl = l - lg * 3u;
+  uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane +
+                   (r * (uint32_t)g.W + cc);
+  const uint16_t* src = p.kv + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts + e;
+
+  __shared__ float red_lo[kStripWaves][64 * 8];
+  __shared__ float red_hi[kStripWaves][64 * 8];
+
+  float mnv[8], inv[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    mnv[i] = 0.f;
+    inv[i] = 0.f;
+  }
+
+  if (n > 0) {
+    // pass 1: column min / max of the strip over the chunk's valid tokens
+    float lo[8], hi[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      lo[i] = __builtin_inff();
+      hi[i] = -__builtin_inff();
+    }
+    for (uint32_t tb0 = 0; tb0 < (uint32_t)n; tb0 += U * rows) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t t = tb0 + u * rows + row;
+        const uint32_t tc = t < (uint32_t)n ? t : (uint32_t)n - 1u;  // a repeated token leaves min / max unchanged
+        v[u] = *reinterpret_cast<const u32x4*>(src + (int64_t)tc * p.ts);  // cached: read again in pass 2
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float x[8];
+        widen_atom<DT>(v[u], x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          lo[i] = __builtin_fminf(lo[i], x[i]);
+          hi[i] = __builtin_fmaxf(hi[i], x[i]);
+        }
+      }
+    }
+    // lanes holding the same atom differ by multiples of sa
+    for (uint32_t m = sa; m < 64u; m <<= 1) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        lo[i] = __builtin_fminf(lo[i], __shfl_xor(lo[i], (int)m));
+        hi[i] = __builtin_fmaxf(hi[i], __shfl_xor(hi[i], (int)m));
+      }
+    }
+    const uint32_t wave = tid >> 6, lane = tid & 63u;
+    if (lane < sa) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        red_lo[wave][lane * 8 + i] = lo[i];
+        red_hi[wave][lane * 8 + i] = hi[i];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float l0 = red_lo[0][a * 8 + i], h0 = red_hi[0][a * 8 + i];
+#pragma unroll
+      for (int w = 1; w < kStripWaves; ++w) {
+        l0 = __builtin_fminf(l0, red_lo[w][a * 8 + i]);
+        h0 = __builtin_fmaxf(h0, red_hi[w][a * 8 + i]);
+      }
+      const GroupParams q = group_params(l0, h0);
+      mnv[i] = q.mn;
+      inv[i] = q.inv;
+      if (row == 0 && active) {
+        float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + e + i);
+        *reinterpret_cast<f32x2*>(mp) = f32x2{q.scale, q.mn};
+      }
+    }
+  }
+
+  // pass 2: quantize and scatter; every tile position of the strip is written
+  for (uint32_t tb0 = 0; tb0 < (uint32_t)g.FG; tb0 += U * rows) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t t = tb0 + u * rows + row;
+      v[u] = u32x4{0u, 0u, 0u, 0u};
+      if (t < (uint32_t)n) v[u] = stream_load<u32x4>(src + (int64_t)t * p.ts);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t t = tb0 + u * rows + row;
+      if (t >= (uint32_t)g.FG || !active) continue;
+      u32x2 o{0u, 0u};
+      if (t < (uint32_t)n) {
+        float x[8];
+        widen_atom<DT>(v[u], x);
+        o.x = pack4(quantize(x[0], mnv[0], inv[0]), quantize(x[1], mnv[1], inv[1]), quantize(x[2], mnv[2], inv[2]),
+                    quantize(x[3], mnv[3], inv[3]));
+        o.y = pack4(quantize(x[4], mnv[4], inv[4]), quantize(x[5], mnv[5], inv[5]), quantize(x[6], mnv[6], inv[6]),
+                    quantize(x[7], mnv[7], inv[7]));
+      }
+      stream_store<u32x2>(code_addr(g, fbase, t), o);
+    }
+  }
+}
+
+kvc_status finish_units(PackParams& p, int64_t units) {
+  if (units > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
+  p.n_units = (uint32_t)units;
+  p.units_per_xcd = (p.n_units + 7u) / 8u;
+  return KVC_OK;
+}
+
+}  // namespace
+
+kvc_status launch_pack(PackParams p, hipStream_t stream) {
+  const Geo& g = p.g;
+  if (p.n_tokens <= 0) return KVC_OK;
+  p.n_chunks = (int32_t)((p.n_tokens + g.T - 1) / g.T);
+  if (g.apt > 1024) return KVC_ERR_UNSUPPORTED;
+
+  for (int mode = 0; mode < 2; ++mode) {
+    p.n_kinds = 0;
+    for (int kind = 0; kind < 2; ++kind)
+      if (g.mode[kind] == mode) p.kinds[p.n_kinds++] = kind;
+    if (p.n_kinds == 0) continue;
+
+    if (mode == KVC_Q_PER_TOKEN) {
+      const int glanes = g.D / 8;
+      if (glanes > 64 || (glanes & (glanes - 1)) != 0) return KVC_ERR_UNSUPPORTED;
+      const int tpp = g.apt >= 256 ? 1 : 256 / g.apt;
+      p.tpp = tpp;
+      p.dapt = make_fastdiv((uint32_t)g.apt);
+#ifdef KVC_PACK_TB
+      p.tb = KVC_PACK_TB;
+#else
+      p.tb = 64;
+#endif
+      p.tbc = (g.FG + p.tb - 1) / p.tb;
+      const kvc_status st = finish_units(p, (int64_t)p.n_chunks * p.n_kinds * 3 * g.LG * p.tbc);
+      if (st != KVC_OK) return st;
+      const dim3 grid(p.units_per_xcd * 8u), block((unsigned)(g.apt * tpp));
+      const bool uniform = g.apt % 64 == 0;
+      if (g.dtype == KVC_F16) {
+        if (uniform)
+          hipLaunchKernelGGL((pack_token_kernel<KVC_F16, true>), grid, block, 0, stream, p);
+        else
+          hipLaunchKernelGGL((pack_token_kernel<KVC_F16, false>), grid, block, 0, stream, p);
+      } else {
+        if (uniform)
+          hipLaunchKernelGGL((pack_token_kernel<KVC_BF16, true>), grid, block, 0, stream, p);
+        else
+          hipLaunchKernelGGL((pack_token_kernel<KVC_BF16, false>), grid, block, 0, stream, p);
+      }
+    } else {
+#ifdef KVC_PACK_STRIP_ATOMS
+      p.strip_atoms = KVC_PACK_STRIP_ATOMS;
+#else
+      p.strip_atoms = 8;  // 64 channels: 128-byte input rows, 64-byte code rows
+#endif
+      p.n_strips = (g.apt + p.strip_atoms - 1) / p.strip_atoms;
+      p.rows = kStripThreads / p.strip_atoms;
+      const kvc_status st = finish_units(p, (int64_t)p.n_chunks * p.n_kinds * 3 * g.LG * p.n_strips);
+      if (st != KVC_OK) return st;
+      const dim3 grid(p.units_per_xcd * 8u), block(kStripThreads);
+      if (g.dtype == KVC_F16)
+        hipLaunchKernelGGL((pack_channel_kernel<KVC_F16>), grid, block, 0, stream, p);
+      else
+        hipLaunchKernelGGL((pack_channel_kernel<KVC_BF16>), grid, block, 0, stream, p);
+    }
+    if (hipGetLastError() != hipSuccess) return KVC_ERR_RUNTIME;
+  }
+  return KVC_OK;
+}
+
+}  // namespace kvc

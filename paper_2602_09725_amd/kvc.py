@@ -1,0 +1,128 @@
+"""ctypes binding of libkvc.so: same names and argument order as include/kvc.h.
+
+Tensors are passed as device pointers (`tensor.data_ptr()`), streams as
+`torch.cuda.Stream.cuda_stream` handles; torch is used for nothing else.
+"""
+import ctypes as C
+import os
+
+KVC_F16, KVC_BF16 = 0, 1
+KVC_Q_PER_CHANNEL, KVC_Q_PER_TOKEN = 0, 1
+KVC_ABI_VERSION = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libkvc.so")
+_lib = None
+
+
+class KvcError(RuntimeError):
+    def __init__(self, status, what):
+        super().__init__(f"{what}: {status_str(status)} (kvc_status {status})")
+        self.status = status
+
+
+class Layout(C.Structure):
+    """kvc_layout"""
+    _fields_ = [("struct_size", C.c_uint32), ("abi_version", C.c_uint32)] + [
+        (n, C.c_int32) for n in ("num_layers", "num_kv_heads", "head_dim", "dtype", "chunk_tokens", "tile_h", "tile_w",
+                                 "tiles_x", "tiles_y", "k_mode", "v_mode")]
+
+    def __init__(self, num_layers, num_kv_heads, head_dim, dtype, chunk_tokens, tile_h, tile_w, tiles_x, tiles_y,
+                 k_mode=KVC_Q_PER_CHANNEL, v_mode=KVC_Q_PER_TOKEN):
+        super().__init__(C.sizeof(Layout), KVC_ABI_VERSION, num_layers, num_kv_heads, head_dim, dtype, chunk_tokens,
+                         tile_h, tile_w, tiles_x, tiles_y, k_mode, v_mode)
+
+
+class Strides(C.Structure):
+    """kvc_strides (elements)"""
+    _fields_ = [("layer_stride", C.c_int64), ("kv_stride", C.c_int64), ("token_stride", C.c_int64)]
+
+
+class HostChunk(C.Structure):
+    """kvc_host_chunk"""
+    _fields_ = [("host_blob", C.c_void_p), ("bytes", C.c_size_t), ("n_tokens", C.c_int64)]
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load(path=None):
+    """Loads the built library; raises if it has not been built (no fallback)."""
+    global _lib
+    if path is None and _lib is not None:
+        return _lib
+    p = path or _LIB_PATH
+    if not os.path.exists(p):
+        raise RuntimeError(f"{p} is missing: build it with `python -m paper_2602_09725_amd.build` "
+                           "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = C.CDLL(p)
+    LP, vp, i64, i32, sz = C.POINTER(Layout), C.c_void_p, C.c_int64, C.c_int32, C.c_size_t
+    lib.kvc_status_str.argtypes = [C.c_int]
+    lib.kvc_status_str.restype = C.c_char_p
+    lib.kvc_layout_validate.argtypes = [LP]
+    lib.kvc_chunk_sizes.argtypes = [LP, C.POINTER(sz), C.POINTER(sz), C.POINTER(i32)]
+    lib.kvc_blob_meta_offset.argtypes = [LP]
+    lib.kvc_blob_meta_offset.restype = sz
+    lib.kvc_pack.argtypes = [LP, vp, Strides, i64, vp, sz, vp, sz, vp]
+    lib.kvc_restore.argtypes = [LP, vp, vp, i64, vp, Strides, vp]
+    lib.kvc_restore_paged.argtypes = [LP, vp, vp, i64, i64, vp, i64, i32, vp, i64, vp, vp]
+    lib.kvc_fetch_pipeline.argtypes = [LP, C.POINTER(HostChunk), i32, C.POINTER(vp), sz, i32, vp, i64, i32, vp, i64,
+                                       vp, vp, vp, C.POINTER(C.c_float)]
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def status_str(status):
+    return load().kvc_status_str(int(status)).decode()
+
+
+def _check(status, what):
+    if status != 0:
+        raise KvcError(status, what)
+
+
+def layout_validate(layout):
+    return load().kvc_layout_validate(C.byref(layout))
+
+
+def chunk_sizes(layout):
+    """-> (frame_bytes, meta_bytes, frames_per_group) of one chunk section."""
+    fb, mb, f = C.c_size_t(), C.c_size_t(), C.c_int32()
+    _check(load().kvc_chunk_sizes(C.byref(layout), C.byref(fb), C.byref(mb), C.byref(f)), "kvc_chunk_sizes")
+    return fb.value, mb.value, f.value
+
+
+def blob_meta_offset(layout):
+    return load().kvc_blob_meta_offset(C.byref(layout))
+
+
+def kvc_pack(layout, kv_ptr, strides, n_tokens, frames_ptr, frames_cap, meta_ptr, meta_cap, stream=0):
+    _check(load().kvc_pack(C.byref(layout), kv_ptr, Strides(*strides), n_tokens, frames_ptr, frames_cap, meta_ptr,
+                           meta_cap, stream), "kvc_pack")
+
+
+def kvc_restore(layout, frames_ptr, meta_ptr, n_tokens, out_ptr, strides, stream=0):
+    _check(load().kvc_restore(C.byref(layout), frames_ptr, meta_ptr, n_tokens, out_ptr, Strides(*strides), stream),
+           "kvc_restore")
+
+
+def kvc_restore_paged(layout, frames_ptr, meta_ptr, first_token, n_tokens, layer_cache_ptrs_dev, num_blocks,
+                      block_size, block_table_ptr, table_len, err_ptr=None, stream=0):
+    _check(load().kvc_restore_paged(C.byref(layout), frames_ptr, meta_ptr, first_token, n_tokens,
+                                    layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr, table_len, err_ptr,
+                                    stream), "kvc_restore_paged")
+
+
+def kvc_fetch_pipeline(layout, chunks, staging_ptrs, staging_bytes, layer_cache_ptrs_dev, num_blocks, block_size,
+                       block_table_ptr, table_len, err_ptr, copy_stream, compute_stream, timed=True):
+    """chunks: list of (host_ptr, bytes, n_tokens).  Returns fetch-to-ready ms when timed, else None."""
+    arr = (HostChunk * len(chunks))(*[HostChunk(p, b, n) for p, b, n in chunks])
+    st = (C.c_void_p * len(staging_ptrs))(*staging_ptrs)
+    ms = C.c_float(0.0)
+    _check(load().kvc_fetch_pipeline(C.byref(layout), arr, len(chunks), st, staging_bytes, len(staging_ptrs),
+                                     layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr, table_len, err_ptr,
+                                     copy_stream, compute_stream, C.byref(ms) if timed else None),
+           "kvc_fetch_pipeline")
+    return ms.value if timed else None

@@ -18,3 +18,15 @@ def oracle():
 
     kvco_py.lib()
     return kvco_py
+
+
+@pytest.fixture(scope="session")
+def kvc_lib():
+    """The built HIP library; built here only if no build is present."""
+    import paper_2602_09725_amd as kvc
+
+    if not os.path.exists(kvc.lib_path()):
+        from paper_2602_09725_amd import build
+
+        build.build()
+    return kvc.load()

@@ -1,0 +1,317 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by
+element, on the same seeded inputs.
+
+Bar: frame bytes (codes and zero fill), {scale, min} pairs and paged placement
+bit-exact; dequantized fp16 / bf16 values within 1 ulp (asserted), and the
+number of values that are not identical is reported (expected 0).
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import kv_synth
+import kvc_harness as hz
+from kvc_harness import oracle
+
+pytestmark = pytest.mark.gpu
+
+TD = {"f16": torch.float16, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib(kvc_lib):
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return kvc_lib
+
+
+def full_check(glo, olo, kv, n_tokens, dtype, block_size=None, table_seed=0, spare_blocks=3, tag=""):
+    """pack -> compare frames/meta; restore contiguous -> compare; restore paged -> compare placement."""
+    hz.say(f"[case] {tag} L={olo.L} H={olo.H} D={olo.D} {dtype} T={olo.T} tile=({olo.th},{olo.tw}) grid=({olo.TX},{olo.TY}) "
+           f"modes=({olo.k_mode},{olo.v_mode}) n_tokens={n_tokens} bs={block_size}")
+    kv_host = kv_synth.to_u16(kv.cpu()).reshape(-1)
+    want_frames, want_meta = oracle.pack(olo, kv_host, n_tokens)
+    frames, meta = hz.gpu_pack(glo, kv, n_tokens)
+    hz.assert_same_bytes("frames", frames.cpu().numpy(), want_frames)
+    hz.assert_same_bytes("meta", meta.cpu().numpy().view(np.uint32), want_meta.view(np.uint32))
+
+    want_out = oracle.restore(olo, want_frames, want_meta, n_tokens)
+    out = hz.gpu_restore(glo, frames, meta, n_tokens, TD[dtype])
+    neq = hz.assert_within_one_ulp("restore", hz.u16(out), want_out)
+    assert neq == 0, f"{neq} restored values differ from the oracle by 1 ulp"
+
+    if block_size:
+        C = olo.H * olo.D
+        n_logical = (n_tokens + block_size - 1) // block_size
+        num_blocks = n_logical + spare_blocks
+        table = kv_synth.make_block_table(n_logical, num_blocks, table_seed)
+        cache = hz.PagedCache(olo.L, num_blocks, block_size, C)
+        hz.gpu_restore_paged(glo, frames, meta, 0, n_tokens, cache, table.cuda())
+        want_caches, _ = hz.oracle_paged(olo, want_frames, want_meta, 0, n_tokens, olo.L, num_blocks, block_size, C,
+                                         table.numpy())
+        assert int(cache.err.item()) == 0
+        for l, (got, want) in enumerate(zip(cache.numpy_layers(), want_caches)):
+            hz.assert_same_bytes(f"paged layer {l}", got, want)
+    return frames, meta
+
+
+SMALL = [
+    # L, H, D, T, th, tw, TX, TY, n_tokens, block_size      (several tiles, ragged last chunk, pad planes)
+    (4, 2, 16, 24, 4, 8, 2, 3, 24 + 13, 4),      # C/8 = 4: many tokens per pass, F = 4
+    (3, 3, 128, 40, 3, 128, 3, 5, 40 * 2 + 1, 16),  # C/8 = 48: 240-thread workgroups, one-token last chunk
+    (5, 8, 128, 96, 8, 128, 4, 8, 96 + 50, 16),  # the benchmark tile, F = 3
+    (2, 8, 128, 64, 16, 64, 2, 4, 64 * 3, 7),    # tile (16,64): rows are half heads; odd block size
+    (7, 32, 128, 20, 8, 512, 2, 2, 33, 16),      # tile (8,512): four heads per row; C/8 = 512 threads
+    (1, 1, 8, 5, 1, 8, 1, 1, 23, 2),             # smallest shapes: one atom per token, F = 5
+    (6, 4, 64, 130, 2, 128, 5, 3, 130 + 77, 32), # non power-of-two F (ceil(130/15) = 9) and grid
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("modes", [(0, 1), (1, 0), (0, 0), (1, 1)])
+@pytest.mark.parametrize("shape", SMALL, ids=[f"s{i}" for i in range(len(SMALL))])
+def test_small_geometries(shape, modes, dtype):
+    L, H, D, T, th, tw, TX, TY, n, bs = shape
+    glo, olo = hz.layouts(L, H, D, dtype, T, th, tw, TX, TY, *modes)
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=1000 + L * 7 + H, device="cuda")
+    full_check(glo, olo, kv, n, dtype, block_size=bs, tag="small")
+
+
+def adversarial_kv(L, H, D, n, dtype):
+    """Values that stress the quantizer: constant groups, +-0, extremes, exact ties, subnormals, huge ranges."""
+    g = torch.Generator().manual_seed(77)
+    kv = torch.randn((L, 2, n, H, D), generator=g, dtype=torch.float32)
+    kv[0, :, :, 0, :] = 1.25                      # constant along everything: range 0 for both groupings
+    kv[0, :, :, 1, :] = -0.0                      # all negative zero
+    kv[0, 0, :, 2, :] = torch.arange(D, dtype=torch.float32) / 4  # per-token: exact quarter steps
+    kv[0, 1, :, 2, 0::2] = 0.0                    # +0 / -0 mix
+    kv[0, 1, :, 2, 1::2] = -0.0
+    kv[0, :, :, 3, :] *= 6e-8 if dtype == torch.float16 else 1e-30   # subnormal fp16 / tiny bf16
+    if H > 4:
+        kv[0, :, :, 4, :] *= 3e4 if dtype == torch.float16 else 1e30   # close to the largest finite values
+        kv[0, :, 0, 4, 0] = 65504.0 if dtype == torch.float16 else 1.5e38   # the range must stay finite in fp32
+        kv[0, :, 1, 4, 0] = -65504.0 if dtype == torch.float16 else -1.5e38
+    if H > 5:
+        # codes land exactly on .5 positions: min 0, max 255 * 2^k, values (j + 0.5) * 2^k
+        j = torch.arange(D, dtype=torch.float32) % 255
+        row = (j + 0.5) * 0.25
+        row[0], row[1] = 0.0, 255 * 0.25
+        kv[0, :, :, 5, :] = row
+    if L > 1:
+        kv[1] = kv[1] * 1e-3 + 7.0                # small range on a large offset
+    if dtype == torch.float16:
+        kv.clamp_(-65504.0, 65504.0)              # inputs must be finite
+    return kv.to(dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("modes", [(0, 1), (1, 0)])
+def test_adversarial_values(dtype, modes):
+    L, H, D, T, n = 3, 8, 128, 48, 48 + 17
+    glo, olo = hz.layouts(L, H, D, dtype, T, 8, 128, 4, 4, *modes)
+    kv = adversarial_kv(L, H, D, n, TD[dtype]).cuda()
+    full_check(glo, olo, kv, n, dtype, block_size=16, tag="adversarial")
+
+
+def test_strided_input_and_output():
+    L, H, D, T, n = 3, 4, 32, 32, 32 + 9
+    C = H * D
+    glo, olo = hz.layouts(L, H, D, "f16", T, 4, 32, 2, 4)
+    kv = kv_synth.make_kv(L, H, D, n, torch.float16, seed=5, device="cuda")
+    ts, ks = 2 * C + 8, (n + 3) * (2 * C + 8)
+    ls = 2 * ks + 64
+    big = torch.full((L * ls + 64,), float("inf"), dtype=torch.float16, device="cuda")  # gaps must never be read
+    view = torch.as_strided(big, (L, 2, n, C), (ls, ks, ts, 1))
+    view.copy_(kv.view(L, 2, n, C))
+    fb, mb, _ = hz.kvc.chunk_sizes(glo)
+    nc = 2
+    frames = torch.empty(nc * fb, dtype=torch.uint8, device="cuda")
+    meta = torch.empty(nc * mb // 4, dtype=torch.float32, device="cuda")
+    hz.kvc.kvc_pack(glo, big.data_ptr(), (ls, ks, ts), n, frames.data_ptr(), nc * fb, meta.data_ptr(), nc * mb,
+                    hz.stream_handle())
+    f2, m2 = hz.gpu_pack(glo, kv, n)
+    torch.cuda.synchronize()
+    assert torch.equal(frames, f2) and torch.equal(meta.view(torch.int32), m2.view(torch.int32))
+    want_f, want_m = oracle.pack(olo, kv_synth.to_u16(kv.cpu()).reshape(-1), n)
+    hz.assert_same_bytes("frames", frames.cpu().numpy(), want_f)
+    # strided output: everything between the tokens stays poison
+    outbuf = torch.full((L * ls + 64,), hz.POISON, dtype=torch.int16, device="cuda")
+    hz.kvc.kvc_restore(glo, frames.data_ptr(), meta.data_ptr(), n, outbuf.data_ptr(), (ls, ks, ts), hz.stream_handle())
+    torch.cuda.synchronize()
+    want = oracle.restore(olo, want_f, want_m, n).reshape(L, 2, n, C)
+    got = torch.as_strided(outbuf, (L, 2, n, C), (ls, ks, ts, 1))
+    hz.assert_same_bytes("strided restore", got.cpu().numpy().view(np.uint16), want)
+    mask = torch.ones_like(outbuf, dtype=torch.bool)
+    torch.as_strided(mask, (L, 2, n, C), (ls, ks, ts, 1)).fill_(False)
+    assert bool((outbuf[mask] == hz.POISON).all())
+
+
+def test_paged_bad_block_ids_and_chunked_calls():
+    """Ids outside the cache are skipped and reported; chunk-at-a-time calls with first_token fill the same cache."""
+    L, H, D, T = 2, 8, 128, 64
+    n, bs = 3 * T + 20, 16
+    C = H * D
+    glo, olo = hz.layouts(L, H, D, "bf16", T, 8, 128, 4, 4)
+    kv = kv_synth.make_kv(L, H, D, n, torch.bfloat16, seed=9, device="cuda")
+    frames, meta = hz.gpu_pack(glo, kv, n)
+    fb, mb, _ = hz.kvc.chunk_sizes(glo)
+    n_logical = (n + bs - 1) // bs
+    num_blocks = n_logical + 5
+    table = kv_synth.make_block_table(n_logical, num_blocks, 3).clone()
+    table[2] = num_blocks       # first id past the cache
+    table[7] = -1
+    table[n_logical - 1] = 2 ** 31 - 1
+    cache = hz.PagedCache(L, num_blocks, bs, C)
+    tab = table.cuda()
+    for c in range(4):  # one call per chunk
+        nt = min(T, n - c * T)
+        hz.gpu_restore_paged(glo, frames[c * fb:(c + 1) * fb], meta[c * mb // 4:(c + 1) * mb // 4], c * T, nt, cache, tab)
+    assert int(cache.err.item()) == 1
+    f_np, m_np = frames.cpu().numpy(), meta.cpu().numpy()
+    want, err = hz.oracle_paged(olo, f_np, m_np, 0, n, L, num_blocks, bs, C, table.numpy())
+    assert err == 1
+    for l, (got, w) in enumerate(zip(cache.numpy_layers(), want)):
+        hz.assert_same_bytes(f"paged layer {l}", got, w)
+    # a clean table leaves the error word alone
+    cache2 = hz.PagedCache(L, num_blocks, bs, C)
+    hz.gpu_restore_paged(glo, frames, meta, 0, n, cache2, kv_synth.make_block_table(n_logical, num_blocks, 3).cuda())
+    assert int(cache2.err.item()) == 0
+
+
+def test_empty_input_is_a_no_op():
+    glo, _ = hz.layouts(2, 8, 128, "f16", 64, 8, 128, 4, 4)
+    sentinel = torch.full((1024,), 0x5A, dtype=torch.uint8, device="cuda")
+    kvc = hz.kvc
+    kvc.kvc_pack(glo, sentinel.data_ptr(), (0, 0, 1024), 0, sentinel.data_ptr(), 0, sentinel.data_ptr(), 0, hz.stream_handle())
+    kvc.kvc_restore(glo, sentinel.data_ptr(), sentinel.data_ptr(), 0, sentinel.data_ptr(), (0, 0, 1024), hz.stream_handle())
+    torch.cuda.synchronize()
+    assert bool((sentinel == 0x5A).all())
+
+
+# ------------------------------------------------------------------ benchmark configurations
+
+
+def test_config_tiny_full():
+    w = kv_synth.WORKLOADS["tiny"]
+    glo, olo = hz.workload_layouts(w)
+    kv = kv_synth.make_workload_kv(w, "cuda")
+    full_check(glo, olo, kv, w.n_tokens, w.dtype, block_size=16, tag=w.name)
+
+
+def test_config_llama3_8b_8k_full():
+    w = kv_synth.WORKLOADS["llama3_8b_8k"]
+    glo, olo = hz.workload_layouts(w)
+    kv = kv_synth.make_workload_kv(w, "cuda")
+    full_check(glo, olo, kv, w.n_tokens, w.dtype, block_size=None, tag=w.name)
+
+
+def chunkwise_check(w, chunk_ids, tag):
+    """Full-size run on the GPU in the benchmark's launch configuration (one pack call, one paged restore call
+    over the whole sequence), compared with the oracle chunk by chunk to bound host memory: chunk sections are
+    independent, so the oracle packs / restores chunk c as a one-chunk problem placed at first_token = c*T."""
+    glo, olo = hz.workload_layouts(w)
+    C, T, bs = w.C, w.T, w.block_size
+    hz.say(f"[case] {tag}: generating {w.L}x2x{w.n_tokens}x{C} {w.dtype}")
+    kv = kv_synth.make_workload_kv(w, "cuda")
+    frames, meta = hz.gpu_pack(glo, kv, w.n_tokens)
+    fb, mb, _ = hz.kvc.chunk_sizes(glo)
+    n_logical = w.n_logical_blocks
+    table = kv_synth.make_block_table(n_logical, n_logical, w.seed)  # a permutation of all blocks
+    cache = hz.PagedCache(w.L, n_logical, bs, C)
+    hz.gpu_restore_paged(glo, frames, meta, 0, w.n_tokens, cache, table.cuda())
+    assert int(cache.err.item()) == 0
+    hz.say(f"[case] {tag}: GPU done, checking chunks {list(chunk_ids)}")
+    table_np = table.numpy()
+    for c in chunk_ids:
+        nt = min(T, w.n_tokens - c * T)
+        kv_c = kv[:, :, c * T:c * T + nt].contiguous().cpu()
+        want_f, want_m = oracle.pack(olo, kv_synth.to_u16(kv_c).reshape(-1), nt)
+        hz.assert_same_bytes(f"frames chunk {c}", frames[c * fb:(c + 1) * fb].cpu().numpy(), want_f)
+        hz.assert_same_bytes(f"meta chunk {c}", meta[c * mb // 4:(c + 1) * mb // 4].cpu().numpy().view(np.uint32),
+                             want_m.view(np.uint32))
+        # oracle restore of this chunk into a private poison cache, then compare the blocks it owns
+        want_caches, err = hz.oracle_paged(olo, want_f, want_m, c * T, nt, w.L, n_logical, bs, C, table_np)
+        assert err == 0
+        b0, b1 = c * T // bs, (c * T + nt + bs - 1) // bs
+        phys = torch.from_numpy(table_np[b0:b1].astype(np.int64))
+        for l in range(w.L):
+            got = cache.layers[l][:, phys.cuda()].cpu().numpy().view(np.uint16)
+            want = want_caches[l].reshape(2, n_logical, bs, C)[:, phys.numpy()]
+            hz.assert_same_bytes(f"paged chunk {c} layer {l}", got, want)
+        hz.say(f"[case] {tag}: chunk {c} ok")
+    # properties that hold at any size: every slot of a mapped position was written, the tail of the last block was not
+    for l in (0, w.L - 1):
+        logical_view = cache.layers[l][:, table.long().cuda()].reshape(2, n_logical * bs, C)
+        assert int((logical_view[:, :w.n_tokens] == hz.POISON).all(dim=-1).sum()) == 0
+        assert bool((logical_view[:, w.n_tokens:] == hz.POISON).all())
+    return kv, frames, meta, cache, table
+
+
+def test_config_llama3_8b_32k_paged():
+    w = kv_synth.WORKLOADS["llama3_8b_32k_paged"]
+    chunkwise_check(w, range(w.n_chunks), w.name)
+
+
+def test_config_yi34b_80k_paged_bf16():
+    w = kv_synth.WORKLOADS["yi34b_80k_paged"]
+    # first chunk, one from the middle, the last full one and the 128-token tail (80000 = 39*2048 + 128)
+    chunkwise_check(w, [0, 19, 38, 39], w.name)
+
+
+def test_config_pipeline_matches_single_call():
+    """16 pinned host blobs, copy on one stream, restore on another: same cache as one kvc_restore_paged call,
+    which the previous tests tie to the oracle; one chunk is also checked against the oracle directly."""
+    w = kv_synth.WORKLOADS["llama3_8b_32k_pipeline"]
+    glo, olo = hz.workload_layouts(w)
+    C, T, bs = w.C, w.T, w.block_size
+    kvc = hz.kvc
+    kv = kv_synth.make_workload_kv(w, "cuda")
+    frames, meta = hz.gpu_pack(glo, kv, w.n_tokens)
+    fb, mb, _ = kvc.chunk_sizes(glo)
+    moff = kvc.blob_meta_offset(glo)
+    blob_bytes = moff + mb
+    assert blob_bytes == 142_868_480
+    blobs = []
+    for c in range(w.n_chunks):
+        b = torch.zeros(blob_bytes, dtype=torch.uint8, pin_memory=True)
+        b[:fb].copy_(frames[c * fb:(c + 1) * fb])
+        b[moff:moff + mb].copy_(meta.view(torch.uint8)[c * mb:(c + 1) * mb])
+        blobs.append(b)
+    n_logical = w.n_logical_blocks
+    table = kv_synth.make_block_table(n_logical, n_logical, w.seed).cuda()
+    ref = hz.PagedCache(w.L, n_logical, bs, C)
+    hz.gpu_restore_paged(glo, frames, meta, 0, w.n_tokens, ref, table)
+    del kv
+    for n_staging in (2, 3):
+        cache = hz.PagedCache(w.L, n_logical, bs, C)
+        staging = [torch.empty(blob_bytes, dtype=torch.uint8, device="cuda") for _ in range(n_staging)]
+        s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        ms = kvc.kvc_fetch_pipeline(glo, [(b.data_ptr(), blob_bytes, T) for b in blobs], [s.data_ptr() for s in staging],
+                                    blob_bytes, cache.ptrs.data_ptr(), n_logical, bs, table.data_ptr(), n_logical,
+                                    cache.err.data_ptr(), s_copy.cuda_stream, s_comp.cuda_stream, timed=True)
+        torch.cuda.synchronize()
+        hz.say(f"[case] pipeline n_staging={n_staging}: fetch-to-ready {ms:.2f} ms")
+        assert ms > 0 and int(cache.err.item()) == 0
+        for l in range(w.L):
+            assert torch.equal(cache.layers[l], ref.layers[l]), f"layer {l} differs from the single-call restore"
+    # untimed form: returns after enqueueing, caller synchronizes
+    cache = hz.PagedCache(w.L, n_logical, bs, C)
+    r = kvc.kvc_fetch_pipeline(glo, [(b.data_ptr(), blob_bytes, T) for b in blobs], [s.data_ptr() for s in staging],
+                               blob_bytes, cache.ptrs.data_ptr(), n_logical, bs, table.data_ptr(), n_logical,
+                               cache.err.data_ptr(), s_copy.cuda_stream, s_comp.cuda_stream, timed=False)
+    assert r is None
+    s_comp.synchronize()
+    torch.cuda.synchronize()
+    for l in (0, w.L - 1):
+        assert torch.equal(cache.layers[l], ref.layers[l])
+    # oracle on chunk 5 straight from the host blob
+    c = 5
+    blob = blobs[c].numpy()
+    want_caches, err = hz.oracle_paged(olo, blob[:fb], blob[moff:moff + mb].view(np.float32), c * T, T, w.L, n_logical,
+                                       bs, C, table.cpu().numpy())
+    phys = table.cpu().long()[c * T // bs:(c + 1) * T // bs]
+    for l in (0, 13, w.L - 1):
+        got = ref.layers[l][:, phys.cuda()].cpu().numpy().view(np.uint16)
+        hz.assert_same_bytes(f"pipeline chunk {c} layer {l}", got, want_caches[l].reshape(2, n_logical, bs, C)[:, phys.numpy()])

@@ -1,0 +1,124 @@
+"""Host-side behaviour of the C ABI that needs no GPU: the library loads, exports
+every symbol the header declares, sizes agree with the oracle's, and every
+host-checkable fault is rejected before anything could be enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_09725_amd as kvc
+from paper_2602_09725_amd import kvc as binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def good(**kw):
+    base = dict(num_layers=32, num_kv_heads=8, head_dim=128, dtype=0, chunk_tokens=2048, tile_h=8, tile_w=128,
+                tiles_x=8, tiles_y=64)
+    base.update(kw)
+    return kvc.Layout(**base)
+
+
+def test_library_exports_every_declared_symbol(kvc_lib):
+    header = open(os.path.join(ROOT, "include", "kvc.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(kvc_[a-z_]+)\s*\(", body))
+    assert {"kvc_pack", "kvc_restore", "kvc_restore_paged", "kvc_fetch_pipeline", "kvc_chunk_sizes",
+            "kvc_layout_validate", "kvc_status_str", "kvc_blob_meta_offset"} <= names
+    for n in names:
+        assert hasattr(kvc_lib, n), f"libkvc.so does not export {n}"
+
+
+def test_binding_struct_matches_header(kvc_lib):
+    assert ctypes.sizeof(kvc.Layout) == 13 * 4
+    assert kvc.layout_validate(good()) == 0
+    lo = good()
+    lo.struct_size = 48
+    assert kvc.layout_validate(lo) == 1
+    lo = good()
+    lo.abi_version = 2
+    assert kvc.layout_validate(lo) == 1
+
+
+def test_chunk_sizes_agree_with_oracle(kvc_lib, oracle):
+    for kw in (dict(), dict(num_layers=60, dtype=1), dict(num_layers=2), dict(k_mode=1, v_mode=0),
+               dict(num_kv_heads=32, tile_h=8, tile_w=512, chunk_tokens=1000, tiles_x=3, tiles_y=7)):
+        lo = good(**kw)
+        fb, mb, F = kvc.chunk_sizes(lo)
+        olo = oracle.make_layout(lo.num_layers, lo.num_kv_heads, lo.head_dim, lo.dtype, lo.chunk_tokens, lo.tile_h,
+                                 lo.tile_w, lo.tiles_x, lo.tiles_y, lo.k_mode, lo.v_mode)
+        assert (fb, mb, F) == (oracle.frame_bytes(olo), 4 * oracle.meta_floats(olo), oracle.frames_per_group(olo))
+        assert kvc.blob_meta_offset(lo) == (fb + 255) // 256 * 256
+    assert kvc.chunk_sizes(good())[:2] == (138_412_032, 4_456_448)
+
+
+@pytest.mark.parametrize("kw", [dict(tile_w=100), dict(num_layers=0), dict(dtype=2), dict(k_mode=3), dict(tiles_x=0),
+                                dict(chunk_tokens=-5), dict(tile_h=16)])
+def test_inconsistent_layouts_rejected(kvc_lib, kw):
+    assert kvc.layout_validate(good(**kw)) == 1
+    with pytest.raises(kvc.KvcError):
+        kvc.chunk_sizes(good(**kw))
+
+
+def test_data_calls_reject_bad_arguments_before_enqueueing(kvc_lib):
+    """Every case returns on the host checks; no pointer is dereferenced and nothing is launched."""
+    lo = good()
+    fb, mb, _ = kvc.chunk_sizes(lo)
+    C = 1024
+    dense = (2 * 4096 * C, 4096 * C, C)
+    A = 0x7F0000000000  # an aligned, never dereferenced address
+
+    def status(fn, *a):
+        try:
+            fn(*a)
+        except kvc.KvcError as e:
+            return e.status
+        return 0
+
+    assert status(kvc.kvc_pack, lo, None, dense, 4096, A, 2 * fb, A, 2 * mb) == 1          # null input
+    assert status(kvc.kvc_pack, lo, A, dense, 4096, A, 2 * fb - 1, A, 2 * mb) == 3         # frames too small
+    assert status(kvc.kvc_pack, lo, A, dense, 4096, A, 2 * fb, A, mb) == 3                 # meta too small
+    assert status(kvc.kvc_pack, lo, A, dense, -1, A, 2 * fb, A, 2 * mb) == 1               # negative count
+    assert status(kvc.kvc_pack, lo, A + 2, dense, 4096, A, 2 * fb, A, 2 * mb) == 1         # misaligned input
+    assert status(kvc.kvc_pack, lo, A, (dense[0], dense[1], C + 4), 4096, A, 2 * fb, A, 2 * mb) == 1  # stride % 8
+    assert status(kvc.kvc_pack, lo, A, (dense[0], dense[1], C - 8), 4096, A, 2 * fb, A, 2 * mb) == 1  # tokens overlap
+    assert status(kvc.kvc_pack, good(head_dim=4, num_kv_heads=256), A, dense, 4096, A, 2 * fb, A, 2 * mb) == 2
+    assert status(kvc.kvc_pack, good(tile_w=4, tile_h=256), A, dense, 4096, A, 2 * fb, A, 2 * mb) == 2
+    assert status(kvc.kvc_restore, lo, A, None, 4096, A, dense) == 1
+    assert status(kvc.kvc_restore, lo, A, A + 4, 4096, A, dense) == 1                      # meta not 8-aligned
+    # paged: first_token must be a chunk boundary, the table must cover the range
+    paged = lambda **k: status(kvc.kvc_restore_paged, lo, A, A, k.get("first", 0), k.get("n", 4096), k.get("cache", A),
+                               k.get("nb", 256), k.get("bs", 16), k.get("table", A), k.get("tl", 256))
+    assert paged(first=100) == 1
+    assert paged(tl=255) == 1
+    assert paged(first=2048, n=4096, tl=256) == 1
+    assert paged(bs=0) == 1
+    assert paged(nb=0) == 1
+    assert paged(cache=None) == 1
+    assert paged(table=None) == 1
+    # pipeline
+    chunks = [(A, kvc.blob_meta_offset(lo) + mb, 2048)] * 3
+    blob = kvc.blob_meta_offset(lo) + mb
+    pipe = lambda **k: status(kvc.kvc_fetch_pipeline, lo, k.get("chunks", chunks), k.get("staging", [A, A + 256]),
+                              k.get("sb", blob), A, 512, 16, A, k.get("tl", 512), None, k.get("cs", 1), k.get("xs", 2))
+    assert pipe(staging=[A]) == 1                          # fewer than two staging slots
+    assert pipe(sb=blob - 1) == 3
+    assert pipe(chunks=[(A, blob - 1, 2048)]) == 3
+    assert pipe(chunks=[(A, blob, 100), (A, blob, 2048)]) == 1   # only the last chunk may be short
+    assert pipe(chunks=[(A, blob, 0)]) == 1
+    assert pipe(cs=5, xs=5) == 1                           # one stream for both roles
+    assert pipe(cs=0) == 1
+    assert pipe(tl=10) == 1
+    assert pipe(staging=[A, A + 8]) == 1                   # staging alignment
+
+
+def test_status_strings(kvc_lib):
+    assert kvc.status_str(0) == "ok"
+    assert {kvc.status_str(i) for i in range(5)}.isdisjoint({"unknown status"})
+    assert kvc.status_str(99) == "unknown status"
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.load(str(tmp_path / "libkvc.so"))
