@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV pack / restore hot path on one MI355X.
+
+One step = kvc_pack of the whole synthetic KV cache (statistics + 8-bit
+quantization + codec-friendly layout) followed by kvc_restore_paged of the
+resulting frames into a paged KV cache (unpack + dequantize + placement), with
+every input already resident in HBM.  Prints ONE JSON line.
+
+  value     : algorithmic bytes of one step / wall time of one step, GB/s
+  roofline  : the slower of the two kernels of a step against the HBM peak,
+              its duration measured with events on the launch stream
+  cpu_baseline : the CPU oracle on a bounded sample of the same workload
+  fetch     : the two-stream pipelined fetch of the same frames from pinned host
+              memory (bound by the host link, never part of `value`)
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(w, frame_bytes, meta_bytes):
+    """Bytes the method itself must move (per launch over the whole workload)."""
+    elems = w.L * 2 * w.n_tokens * w.C
+    frames = w.n_chunks * frame_bytes          # codes + zero planes of layers beyond L
+    meta = w.n_chunks * meta_bytes
+    pack = 2 * elems + frames + meta           # read KV once, write every frame byte and every pair
+    restore = elems + meta + 2 * elems         # read the codes and pairs of valid tokens, write the cache
+    return elems, pack, restore
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b_32k_paged")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-fetch", action="store_true")
+    ap.add_argument("--cpu-sample-chunks", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import kv_synth
+    import paper_2602_09725_amd as kvc
+
+    if not torch.cuda.is_available():
+        print("bench.py: needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(kvc.lib_path()):
+        from paper_2602_09725_amd import build
+        build.build()
+    kvc.load()
+
+    w = kv_synth.WORKLOADS[args.workload]
+    dt = 0 if w.dtype == "f16" else 1
+    lo = kvc.Layout(w.L, w.H, w.D, dt, w.T, w.th, w.tw, w.TX, w.TY)
+    fb, mb, F = kvc.chunk_sizes(lo)
+    elems, pack_bytes, restore_bytes = algorithmic_bytes(w, fb, mb)
+    C, bs = w.C, w.block_size
+    dev = "cuda"
+
+    kv = kv_synth.make_workload_kv(w, dev)
+    frames = torch.empty(w.n_chunks * fb, dtype=torch.uint8, device=dev)
+    meta = torch.empty(w.n_chunks * mb, dtype=torch.uint8, device=dev)
+    n_logical = w.n_logical_blocks
+    table = kv_synth.make_block_table(n_logical, n_logical, w.seed, dev)
+    layers = [torch.empty((2, n_logical, bs, C), dtype=torch.int16, device=dev) for _ in range(w.L)]
+    ptrs = torch.tensor([t.data_ptr() for t in layers], dtype=torch.int64, device=dev)
+    err = torch.zeros(1, dtype=torch.int32, device=dev)
+    strides = (2 * w.n_tokens * C, w.n_tokens * C, C)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        kvc.kvc_pack(lo, kv.data_ptr(), strides, w.n_tokens, frames.data_ptr(), frames.numel(), meta.data_ptr(),
+                     meta.numel(), sh)
+        if ev:
+            ev[1].record(stream)
+        kvc.kvc_restore_paged(lo, frames.data_ptr(), meta.data_ptr(), 0, w.n_tokens, ptrs.data_ptr(), n_logical, bs,
+                              table.data_ptr(), n_logical, err.data_ptr(), sh)
+        if ev:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert int(err.item()) == 0
+    ms_per_step = wall * 1e3 / args.steps
+    pack_ms = [e[0].elapsed_time(e[1]) for e in events]
+    rest_ms = [e[1].elapsed_time(e[2]) for e in events]
+    pack_avg, rest_avg = sum(pack_ms) / len(pack_ms), sum(rest_ms) / len(rest_ms)
+
+    def roof(name, nbytes, avg_ms, all_ms):
+        gbps = nbytes / (avg_ms * 1e-3) / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None, "avg_ms": round(avg_ms, 4),
+                "min_ms": round(min(all_ms), 4), "algorithmic_bytes": nbytes}
+
+    roof_pack = roof("pack_kernel (kvc_pack)", pack_bytes, pack_avg, pack_ms)
+    roof_rest = roof("restore_kernel (kvc_restore_paged)", restore_bytes, rest_avg, rest_ms)
+    dominant, other = (roof_pack, roof_rest) if pack_avg >= rest_avg else (roof_rest, roof_pack)
+
+    # a plain device copy of the same size as the restore output: the practical streaming ceiling of this machine
+    a = torch.empty(restore_bytes // 3, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    for _ in range(2):
+        b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(5):
+        b.copy_(a)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbps = 2 * a.numel() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+
+    out = {
+        "metric": "KV restore/pack GB/s at 1 MI355X + % of HBM peak; 32K-token fetch-to-ready ms",
+        "value": round((pack_bytes + restore_bytes) / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.L, "kv_heads": w.H, "head_dim": w.D, "tokens": w.n_tokens,
+                   "kv_dtype": w.dtype, "chunk_tokens": w.T, "tile": [w.th, w.tw], "tile_grid": [w.TX, w.TY],
+                   "frames_per_group": F, "block_size": bs, "elements": elems,
+                   "step": "kvc_pack + kvc_restore_paged, inputs resident in HBM"},
+        "roofline": dominant,
+        "roofline_other_kernel": other,
+        "pct_of_hbm_peak": {"restore": round(100 * roof_rest["frac"], 2), "pack": round(100 * roof_pack["frac"], 2)},
+        "device_copy_GBps": round(copy_gbps, 1),
+    }
+
+    # ---- pipelined fetch from pinned host memory (the host link is the bound)
+    if not args.skip_fetch:
+        moff = kvc.blob_meta_offset(lo)
+        blob_bytes = moff + mb
+        blobs = []
+        for c in range(w.n_chunks):
+            hb = torch.zeros(blob_bytes, dtype=torch.uint8, pin_memory=True)
+            hb[:fb].copy_(frames[c * fb:(c + 1) * fb])
+            hb[moff:moff + mb].copy_(meta[c * mb:(c + 1) * mb])
+            blobs.append(hb)
+        n_staging = 3
+        staging = [torch.empty(blob_bytes, dtype=torch.uint8, device=dev) for _ in range(n_staging)]
+        s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+        chunks = [(hb.data_ptr(), blob_bytes, min(w.T, w.n_tokens - c * w.T)) for c, hb in enumerate(blobs)]
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(4):
+            times.append(kvc.kvc_fetch_pipeline(lo, chunks, [s.data_ptr() for s in staging], blob_bytes,
+                                                ptrs.data_ptr(), n_logical, bs, table.data_ptr(), n_logical,
+                                                err.data_ptr(), s_copy.cuda_stream, s_comp.cuda_stream, timed=True))
+            torch.cuda.synchronize()
+        # bare copies of the same blobs, nothing else running
+        h0, h1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        bare = []
+        for _ in range(3):
+            h0.record(stream)
+            for c, hb in enumerate(blobs):
+                staging[c % n_staging].copy_(hb, non_blocking=True)
+            h1.record(stream)
+            torch.cuda.synchronize()
+            bare.append(h0.elapsed_time(h1))
+        total = blob_bytes * len(blobs)
+        out["fetch"] = {"workload": "llama3_8b_32k_pipeline", "chunks": len(blobs), "blob_bytes": blob_bytes,
+                        "n_staging": n_staging, "fetch_to_ready_ms": round(min(times[1:]), 3),
+                        "fetch_to_ready_ms_all": [round(t, 3) for t in times],
+                        "bare_h2d_ms": round(min(bare), 3),
+                        "h2d_GBps": round(total / (min(bare) * 1e-3) / 1e9, 2),
+                        "pcie_inclusive_restore_GBps": round(restore_bytes / (min(times[1:]) * 1e-3) / 1e9, 1)}
+        del blobs, staging
+
+    # ---- the CPU oracle on a bounded sample of the same workload (rank 0, N = 1)
+    if not args.skip_cpu_baseline:
+        from oracle import kvco_py as oracle
+
+        sc = min(args.cpu_sample_chunks, w.n_chunks)
+        nt = min(sc * w.T, w.n_tokens)
+        olo = oracle.make_layout(w.L, w.H, w.D, dt, w.T, w.th, w.tw, w.TX, w.TY)
+        kv_host = kv_synth.to_u16(kv[:, :, :nt].contiguous().cpu()).reshape(-1)
+        nb = (nt + bs - 1) // bs
+        caches = [np.empty(2 * nb * bs * C, dtype=np.uint16) for _ in range(w.L)]
+        tab = np.random.default_rng(w.seed).permutation(nb).astype(np.int32)
+        c0 = time.perf_counter()
+        f_o, m_o = oracle.pack(olo, kv_host, nt)
+        c1 = time.perf_counter()
+        oracle.restore_paged(olo, f_o, m_o, 0, nt, caches, nb, bs, tab)
+        c2 = time.perf_counter()
+        frac = nt / w.n_tokens
+        out["cpu_baseline"] = {
+            "value": round((pack_bytes + restore_bytes) * frac / (c2 - c0) / 1e9, 3), "unit": "GB/s",
+            "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {nt} of {w.n_tokens} tokens ({sc} of {w.n_chunks} chunks), all {w.L} layers, K and V: "
+                      f"oracle pack {c1 - c0:.2f} s + paged restore {c2 - c1:.2f} s",
+            "pack_GBps": round(pack_bytes * frac / (c1 - c0) / 1e9, 3),
+            "restore_GBps": round(restore_bytes * frac / (c2 - c1) / 1e9, 3)}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

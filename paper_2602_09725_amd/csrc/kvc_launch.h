@@ -42,17 +42,20 @@ struct PackParams {
   int32_t n_chunks;
   uint8_t* frames;
   float* meta;
-  // per-token kernel
+  // workgroups of per-token kinds: blocks of tb token positions
   int32_t tb, tbc, tpp;
   FastDiv dapt;
-  // per-channel kernel
-  int32_t strip_atoms;    // atoms (8 channels each) per strip
+  int32_t n_kinds_tok;
+  int32_t kinds_tok[2];
+  // workgroups of per-channel kinds: strips of channels
+  int32_t strip_atoms;    // atoms (8 channels each) per strip, a power of two <= 16
   int32_t n_strips;
   int32_t rows;           // token rows per pass = threads / strip_atoms
-  // common
-  int32_t n_kinds;        // kinds handled by this launch
-  int32_t kinds[2];
-  uint32_t n_units;
+  int32_t n_kinds_ch;
+  int32_t kinds_ch[2];
+  // work units of the two kinds of workgroup and their share per XCD
+  uint32_t n_units_ch, n_units_tok;
+  uint32_t ch_per_xcd, tok_per_xcd;
   uint32_t units_per_xcd;
 };
 

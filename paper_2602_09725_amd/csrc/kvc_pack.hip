@@ -1,7 +1,8 @@
 // Pack kernels: group statistics, 8-bit quantization and the codec-friendly
 // layout (Sec. 3.2.1 steps 1-3, Sec. 3.2.2, Sec. 4 item (1)).
 //
-// Two kernels, one per quantization grouping:
+// One launch covers both quantization groupings; a workgroup takes one of two
+// bodies according to the grouping of the kind it works on:
 //  * per-token groups (one group = the D elements of one head of one token):
 //    statistics, quantization and the layout scatter fused in one pass.  A thread
 //    holds an atom of 8 consecutive elements; the D/8 lanes of a head reduce
@@ -80,19 +81,18 @@ __device__ __forceinline__ uint8_t* code_addr(const Geo& g, uint8_t* fbase, uint
 // ------------------------------------------------------------ per-token groups
 
 template <int DT, bool UNIFORM>
-__global__ void __launch_bounds__(1024) pack_token_kernel(const PackParams p) {
+__device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t unit) {
   constexpr int U = KVC_PACK_U;
   const Geo& g = p.g;
-  const uint32_t unit = (blockIdx.x & 7u) * p.units_per_xcd + (blockIdx.x >> 3);
-  if (unit >= p.n_units) return;
   uint32_t uu = unit;
   const uint32_t tbi = uu % (uint32_t)p.tbc;
   uu /= (uint32_t)p.tbc;
   const uint32_t l3 = (uint32_t)(3 * g.LG);
   const uint32_t l = uu % l3;
   uu /= l3;
-  const uint32_t kind = (uint32_t)p.kinds[uu % (uint32_t)p.n_kinds];
-  const uint32_t c = uu / (uint32_t)p.n_kinds;
+  const uint32_t kind = (uint32_t)p.kinds_tok[uu % (uint32_t)p.n_kinds_tok];
+  const uint32_t c = uu / (uint32_t)p.n_kinds_tok;
+  if (threadIdx.x >= (uint32_t)(g.apt * p.tpp)) return;  // the block is rounded up to whole waves
 
   const uint32_t tid = threadIdx.x;
   uint32_t tsub = fd_div(p.dapt, tid);
@@ -163,23 +163,22 @@ __global__ void __launch_bounds__(1024) pack_token_kernel(const PackParams p) {
 
 // ---------------------------------------------------------- per-channel groups
 
-constexpr int kStripThreads = 256;
-constexpr int kStripWaves = kStripThreads / 64;
+constexpr int kMaxWaves = 16;       // 1024 threads
+constexpr int kMaxStripAtoms = 16;  // 128 channels
 
 template <int DT>
-__global__ void __launch_bounds__(kStripThreads) pack_channel_kernel(const PackParams p) {
+__device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t unit, float (*red_lo)[kMaxStripAtoms * 8],
+                                                  float (*red_hi)[kMaxStripAtoms * 8]) {
   constexpr int U = KVC_PACK_U;
   const Geo& g = p.g;
-  const uint32_t unit = (blockIdx.x & 7u) * p.units_per_xcd + (blockIdx.x >> 3);
-  if (unit >= p.n_units) return;
   uint32_t uu = unit;
   const uint32_t strip = uu % (uint32_t)p.n_strips;
   uu /= (uint32_t)p.n_strips;
   const uint32_t l3 = (uint32_t)(3 * g.LG);
   const uint32_t l = uu % l3;
   uu /= l3;
-  const uint32_t kind = (uint32_t)p.kinds[uu % (uint32_t)p.n_kinds];
-  const uint32_t c = uu / (uint32_t)p.n_kinds;
+  const uint32_t kind = (uint32_t)p.kinds_ch[uu % (uint32_t)p.n_kinds_ch];
+  const uint32_t c = uu / (uint32_t)p.n_kinds_ch;
 
   const uint32_t tid = threadIdx.x;
   const uint32_t sa = (uint32_t)p.strip_atoms;  // power of two <= 64
@@ -201,9 +200,6 @@ __global__ void __launch_bounds__(kStripThreads) pack_channel_kernel(const PackP
   uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane +
                    (r * (uint32_t)g.W + cc);
   const uint16_t* src = p.kv + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts + e;
-
-  __shared__ float red_lo[kStripWaves][64 * 8];
-  __shared__ float red_hi[kStripWaves][64 * 8];
 
   float mnv[8], inv[8];
 #pragma unroll
@@ -248,6 +244,7 @@ __global__ void __launch_bounds__(kStripThreads) pack_channel_kernel(const PackP
       }
     }
     const uint32_t wave = tid >> 6, lane = tid & 63u;
+    const uint32_t n_waves = blockDim.x >> 6;
     if (lane < sa) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -259,8 +256,7 @@ __global__ void __launch_bounds__(kStripThreads) pack_channel_kernel(const PackP
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float l0 = red_lo[0][a * 8 + i], h0 = red_hi[0][a * 8 + i];
-#pragma unroll
-      for (int w = 1; w < kStripWaves; ++w) {
+      for (uint32_t w = 1; w < n_waves; ++w) {
         l0 = __builtin_fminf(l0, red_lo[w][a * 8 + i]);
         h0 = __builtin_fmaxf(h0, red_hi[w][a * 8 + i]);
       }
@@ -301,11 +297,21 @@ __global__ void __launch_bounds__(kStripThreads) pack_channel_kernel(const PackP
   }
 }
 
-kvc_status finish_units(PackParams& p, int64_t units) {
-  if (units > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
-  p.n_units = (uint32_t)units;
-  p.units_per_xcd = (p.n_units + 7u) / 8u;
-  return KVC_OK;
+template <int DT, bool UNIFORM>
+__global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
+  __shared__ float red_lo[kMaxWaves][kMaxStripAtoms * 8];
+  __shared__ float red_hi[kMaxWaves][kMaxStripAtoms * 8];
+  // Workgroups go to the 8 XCDs round-robin.  Each XCD gets one contiguous range
+  // of the per-channel units and one of the per-token units, so neighbouring
+  // strips and token blocks share an L2 and every XCD has the same mix of work.
+  const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
+  if (idx < p.ch_per_xcd) {
+    const uint32_t unit = xcd * p.ch_per_xcd + idx;
+    if (unit < p.n_units_ch) pack_channel_body<DT>(p, unit, red_lo, red_hi);
+  } else {
+    const uint32_t unit = xcd * p.tok_per_xcd + (idx - p.ch_per_xcd);
+    if (unit < p.n_units_tok) pack_token_body<DT, UNIFORM>(p, unit);
+  }
 }
 
 }  // namespace
@@ -315,59 +321,56 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
   if (p.n_tokens <= 0) return KVC_OK;
   p.n_chunks = (int32_t)((p.n_tokens + g.T - 1) / g.T);
   if (g.apt > 1024) return KVC_ERR_UNSUPPORTED;
-
-  for (int mode = 0; mode < 2; ++mode) {
-    p.n_kinds = 0;
-    for (int kind = 0; kind < 2; ++kind)
-      if (g.mode[kind] == mode) p.kinds[p.n_kinds++] = kind;
-    if (p.n_kinds == 0) continue;
-
-    if (mode == KVC_Q_PER_TOKEN) {
-      const int glanes = g.D / 8;
-      if (glanes > 64 || (glanes & (glanes - 1)) != 0) return KVC_ERR_UNSUPPORTED;
-      const int tpp = g.apt >= 256 ? 1 : 256 / g.apt;
-      p.tpp = tpp;
-      p.dapt = make_fastdiv((uint32_t)g.apt);
-#ifdef KVC_PACK_TB
-      p.tb = KVC_PACK_TB;
-#else
-      p.tb = 64;
-#endif
-      p.tbc = (g.FG + p.tb - 1) / p.tb;
-      const kvc_status st = finish_units(p, (int64_t)p.n_chunks * p.n_kinds * 3 * g.LG * p.tbc);
-      if (st != KVC_OK) return st;
-      const dim3 grid(p.units_per_xcd * 8u), block((unsigned)(g.apt * tpp));
-      const bool uniform = g.apt % 64 == 0;
-      if (g.dtype == KVC_F16) {
-        if (uniform)
-          hipLaunchKernelGGL((pack_token_kernel<KVC_F16, true>), grid, block, 0, stream, p);
-        else
-          hipLaunchKernelGGL((pack_token_kernel<KVC_F16, false>), grid, block, 0, stream, p);
-      } else {
-        if (uniform)
-          hipLaunchKernelGGL((pack_token_kernel<KVC_BF16, true>), grid, block, 0, stream, p);
-        else
-          hipLaunchKernelGGL((pack_token_kernel<KVC_BF16, false>), grid, block, 0, stream, p);
-      }
-    } else {
-#ifdef KVC_PACK_STRIP_ATOMS
-      p.strip_atoms = KVC_PACK_STRIP_ATOMS;
-#else
-      p.strip_atoms = 8;  // 64 channels: 128-byte input rows, 64-byte code rows
-#endif
-      p.n_strips = (g.apt + p.strip_atoms - 1) / p.strip_atoms;
-      p.rows = kStripThreads / p.strip_atoms;
-      const kvc_status st = finish_units(p, (int64_t)p.n_chunks * p.n_kinds * 3 * g.LG * p.n_strips);
-      if (st != KVC_OK) return st;
-      const dim3 grid(p.units_per_xcd * 8u), block(kStripThreads);
-      if (g.dtype == KVC_F16)
-        hipLaunchKernelGGL((pack_channel_kernel<KVC_F16>), grid, block, 0, stream, p);
-      else
-        hipLaunchKernelGGL((pack_channel_kernel<KVC_BF16>), grid, block, 0, stream, p);
-    }
-    if (hipGetLastError() != hipSuccess) return KVC_ERR_RUNTIME;
+  p.n_kinds_ch = p.n_kinds_tok = 0;
+  for (int kind = 0; kind < 2; ++kind) {
+    if (g.mode[kind] == KVC_Q_PER_CHANNEL)
+      p.kinds_ch[p.n_kinds_ch++] = kind;
+    else
+      p.kinds_tok[p.n_kinds_tok++] = kind;
   }
-  return KVC_OK;
+  // per-token part: a whole number of tokens per pass, about 256 threads
+  const int glanes = g.D / 8;
+  if (p.n_kinds_tok > 0 && (glanes > 64 || (glanes & (glanes - 1)) != 0)) return KVC_ERR_UNSUPPORTED;
+  p.tpp = g.apt >= 256 ? 1 : 256 / g.apt;
+  p.dapt = make_fastdiv((uint32_t)g.apt);
+  const int threads = (g.apt * p.tpp + 63) / 64 * 64;
+#ifdef KVC_PACK_TB
+  p.tb = KVC_PACK_TB;
+#else
+  p.tb = 64;
+#endif
+  p.tbc = (g.FG + p.tb - 1) / p.tb;
+  // per-channel part: strips of 8*strip_atoms channels
+#ifdef KVC_PACK_STRIP_ATOMS
+  p.strip_atoms = KVC_PACK_STRIP_ATOMS;
+#else
+  p.strip_atoms = 8;  // 64 channels: 128-byte input rows, 64-byte code rows
+#endif
+  p.n_strips = (g.apt + p.strip_atoms - 1) / p.strip_atoms;
+  p.rows = threads / p.strip_atoms;
+  const int64_t per_kind = (int64_t)p.n_chunks * 3 * g.LG;
+  const int64_t units_ch = per_kind * p.n_kinds_ch * p.n_strips;
+  const int64_t units_tok = per_kind * p.n_kinds_tok * p.tbc;
+  if (units_ch + units_tok > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
+  p.n_units_ch = (uint32_t)units_ch;
+  p.n_units_tok = (uint32_t)units_tok;
+  p.ch_per_xcd = (p.n_units_ch + 7u) / 8u;
+  p.tok_per_xcd = (p.n_units_tok + 7u) / 8u;
+  p.units_per_xcd = p.ch_per_xcd + p.tok_per_xcd;
+  const dim3 grid(p.units_per_xcd * 8u), block((unsigned)threads);
+  const bool uniform = g.apt % 64 == 0;
+  if (g.dtype == KVC_F16) {
+    if (uniform)
+      hipLaunchKernelGGL((pack_kernel<KVC_F16, true>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((pack_kernel<KVC_F16, false>), grid, block, 0, stream, p);
+  } else {
+    if (uniform)
+      hipLaunchKernelGGL((pack_kernel<KVC_BF16, true>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((pack_kernel<KVC_BF16, false>), grid, block, 0, stream, p);
+  }
+  return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_RUNTIME;
 }
 
 }  // namespace kvc
