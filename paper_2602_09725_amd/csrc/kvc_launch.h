@@ -16,9 +16,15 @@ struct RestoreParams {
   int32_t tb;             // tokens per workgroup (0: library default)
   int32_t tbc;            // token blocks per chunk
   int32_t tpp;            // tokens per pass of a workgroup = threads / apt
+  int32_t tstart;         // first token of workgroup i of a chunk = i * tstart
+  int32_t tstride;        // tokens between consecutive passes of a workgroup
   uint32_t n_units;       // n_chunks * 2 * L * tbc workgroups with work
   uint32_t units_per_xcd;
-  FastDiv dapt;
+  FastDiv dtbc, dL;       // unit -> (token block, layer, kind, chunk)
+  FastDiv dapt;           // atoms per token
+  FastDiv dwpt;           // waves per token (apt / 64) when apt is a multiple of 64
+  uint32_t frame_stride;     // bytes from a frame to the next of the same layer group: 3 planes
+  uint32_t tile_row_stride;  // bytes from a row of tiles to the next: th * W
   // contiguous destination
   uint16_t* out;
   int64_t ls, ks, ts;

@@ -9,18 +9,25 @@
 // Work decomposition.  An "atom" is 8 consecutive elements of a token's H*D
 // vector: 8 code bytes in one frame row (tile_w % 8 == 0) that belong to one
 // head (head_dim % 8 == 0), restored to 16 contiguous bytes.  A workgroup owns a
-// contiguous block of tokens of one (chunk, kind, layer); thread i keeps atom
-// i % (C/8) for the whole block, so
-//   - a wave's load covers 512 contiguous code bytes and its store 1024
-//     contiguous output bytes (full cache lines both ways),
+// contiguous block of tokens of one (chunk, kind, layer); a thread keeps one atom
+// for the whole block, so
+//   - a wave's store covers 1024 contiguous output bytes and its load whole
+//     128-byte (or longer) runs of a frame row: full cache lines both ways,
 //   - per-channel scale/min of the thread's 8 channels are loaded once and stay
-//     in 16 VGPRs,
-//   - when C/8 is a multiple of 64 the token index is wave-uniform and all
-//     index arithmetic (frame, tile position, cache slot, block-table lookup)
-//     runs on the scalar unit.
+//     in 16 VGPRs.
 // A contiguous block of tokens touches F frames at TX-adjacent tile positions,
-// i.e. a few contiguous runs of th rows in each of F planes (Sec. 3.2.1 step 3),
-// so both sides of the copy stay DRAM-page friendly.
+// i.e. a few contiguous runs of th rows in each of F planes (Sec. 3.2.1 step 3).
+//
+// Two bodies:
+//  * "waves" (C/8 a multiple of 64, every model shape of the paper): a wave works
+//    on one token at a time, so everything that depends on the token only (frame,
+//    tile position, cache slot, block-table entry, pair address) is the same for
+//    all its lanes.  Lane k of the wave computes those values for the wave's k-th
+//    token, all tokens at once, and the loop over tokens fetches them with
+//    v_readlane.  The per-token cost is then a handful of instructions; with the
+//    index arithmetic in the loop the kernel is bound by instruction issue, not by
+//    HBM.
+//  * "lanes" (any other C): every lane does its own index arithmetic.
 #include <hip/hip_runtime.h>
 
 #include "kvc_device.h"
@@ -29,149 +36,251 @@
 namespace kvc {
 
 #ifndef KVC_RESTORE_U
-#define KVC_RESTORE_U 8  // token passes in flight per thread
+#define KVC_RESTORE_U 8  // tokens in flight per wave
+#endif
+#ifndef KVC_RESTORE_TB
+#define KVC_RESTORE_TB 32  // tokens per workgroup ("waves" body)
+#endif
+#ifndef KVC_RESTORE_TB_LANES
+#define KVC_RESTORE_TB_LANES 128  // tokens per workgroup ("lanes" body)
 #endif
 
 namespace {
 
-template <int MODE, int DT, bool PAGED, bool UNIFORM>
-__device__ __forceinline__ void restore_body(const RestoreParams& p, uint32_t c, uint32_t kind, uint32_t l,
-                                             uint32_t tbi) {
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, uint32_t k) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)k);
+}
+
+// 8 codes -> 8 dequantized 16-bit values, one 16-byte store.
+template <int MODE, int DT>
+__device__ __forceinline__ void dequant_store(uint16_t* dst, u32x2 code, const float (&sc)[8], const float (&mn)[8],
+                                              f32x2 sm) {
+  float x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t w = i < 4 ? code.x : code.y;
+    const float q = (float)((w >> (8 * (i & 3))) & 0xffu);
+    x[i] = MODE == KVC_Q_PER_CHANNEL ? __builtin_fmaf(q, sc[i], mn[i]) : __builtin_fmaf(q, sm.x, sm.y);
+    // The dequantized value is defined as the binary32 fma result, then rounded
+    // to 16 bits.  Keep the two roundings apart: a mixed-precision fma that
+    // rounds the exact sum straight to fp16 differs in about 1 value in 10^4.
+    asm("" : "+v"(x[i]));
+  }
+  u32x4 o;
+  o.x = narrow_pair<DT>(x[0], x[1]);
+  o.y = narrow_pair<DT>(x[2], x[3]);
+  o.z = narrow_pair<DT>(x[4], x[5]);
+  o.w = narrow_pair<DT>(x[6], x[7]);
+  stream_store<u32x4>(dst, o);
+}
+
+// Scale/min of the 8 channels of atom e (per-channel grouping).
+__device__ __forceinline__ void load_channel_pairs(const float* mbase, int64_t first_pair, float (&sc)[8], float (&mn)[8]) {
+  const KVC_GLOBAL f32x2* mp = (const KVC_GLOBAL f32x2*)(mbase + 2 * first_pair);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const f32x2 v = mp[i];
+    sc[i] = v.x;
+    mn[i] = v.y;
+  }
+}
+
+// ----------------------------------------------------------------- "waves" body
+
+template <int MODE, int DT, bool PAGED>
+__device__ __forceinline__ void restore_body_waves(const RestoreParams& p, uint32_t c, uint32_t kind, uint32_t l,
+                                                   uint32_t tbi) {
   constexpr int U = KVC_RESTORE_U;
   const Geo& g = p.g;
-  const uint32_t tid = threadIdx.x;
-  uint32_t tsub = fd_div(p.dapt, tid);
-  const uint32_t ca = tid - tsub * (uint32_t)g.apt;
-  if (UNIFORM) tsub = wave_uniform(tsub);
-  const uint32_t e = ca * 8u;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t wave = wave_uniform(threadIdx.x >> 6);
+  const uint32_t tsub = fd_div(p.dwpt, wave);              // which token of a pass this wave takes
+  const uint32_t wslab = wave - tsub * p.dwpt.d;           // which 64-atom part of the token
+  const uint32_t e = (wslab * 64u + lane) * 8u;            // first element of the lane's atom
 
   const int64_t chunk_first = (int64_t)c * g.T;
   const int64_t left = p.n_tokens - chunk_first;
   const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;  // valid tokens of this chunk
+  // Tokens of this workgroup: passes k = 0, 1, ... take tokens t0 + k * tstride (+ tsub),
+  // up to t1.  Blocked: one run of tb tokens.  Interleaved: the workgroups of a
+  // (chunk, kind, layer) sweep it together, each taking every nw-th pass.
+  const int32_t t0 = (int32_t)tbi * p.tstart;
+  const int32_t t1 = p.tstride == p.tpp ? (t0 + p.tb < n ? t0 + p.tb : n) : n;
+  if (t0 >= t1) return;
+
+  // ---- per-token values, one token per lane
+  const int32_t t = t0 + (int32_t)tsub + (int32_t)lane * p.tstride;
+  const bool in_range = t < t1;
+  const uint32_t tc = (uint32_t)(in_range ? t : t1 - 1);  // clamp: loads of dead passes stay in bounds
+  // inter-frame layout: token -> (frame of its group, tile position of its group)
+  uint32_t gi, f, ty, tx;
+  fd_divmod(g.dF, tc, gi, f);
+  fd_divmod(g.dTX, gi, ty, tx);
+  const uint32_t src_tok = f * p.frame_stride + ty * p.tile_row_stride + tx * (uint32_t)g.tw;  // bytes inside the section
+  uint64_t dst_tok;  // bytes from the layer's (kind) base
+  bool ok = in_range;
+  if (PAGED) {
+    uint32_t b, slot;
+    fd_divmod(p.dbs, (uint32_t)(p.first_token + chunk_first) + tc, b, slot);
+    const int32_t phys = as_const(p.table)[b];
+    const bool in_cache = (uint32_t)phys < (uint32_t)p.num_blocks;
+    // an id outside the cache: skip the block's writes and report it (Sec. 3.3.2 placement)
+    if (in_range && !in_cache && wslab == 0 && p.err) atomicOr(p.err, 1u);
+    ok = in_range && in_cache;
+    dst_tok = ((uint64_t)(in_cache ? (uint32_t)phys : 0u) * p.dbs.d + slot) * (uint32_t)g.C * 2u;
+  } else {
+    dst_tok = (uint64_t)tc * (uint64_t)p.ts * 2u;
+  }
+  const uint64_t live_mask = __ballot(ok);
+  const uint32_t passes = (uint32_t)__popcll(__ballot(in_range));  // in_range is a prefix of the lanes
+  const uint32_t dst_lo = (uint32_t)dst_tok, dst_hi = (uint32_t)(dst_tok >> 32);
+
+  // ---- per-lane constants
+  uint32_t r, cc;
+  fd_divmod(g.dtw, e, r, cc);  // intra-frame layout: element -> (row, column) of the tile
+  const uint32_t lg = l / 3u, pl = l - lg * 3u;
+  const uint8_t* fsec = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane;
+  const uint32_t src_lane = r * (uint32_t)g.W + cc;
+  const float* mbase = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind];
+  float sc[8], mn[8];
+  const uint8_t* mrow = nullptr;
+  if (MODE == KVC_Q_PER_CHANNEL) {
+    load_channel_pairs(mbase, (int64_t)l * g.C + e, sc, mn);
+  } else {
+    mrow = reinterpret_cast<const uint8_t*>(mbase + 2 * ((int64_t)l * g.T * g.H + fd_div(g.dD, e)));
+  }
+  uint8_t* obase;
+  if (PAGED)
+    obase = reinterpret_cast<uint8_t*>(as_const(p.layer_cache)[l]) + ((int64_t)kind * p.num_blocks * p.dbs.d * g.C + e) * 2;
+  else
+    obase = reinterpret_cast<uint8_t*>(p.out + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts + e);
+
+  // ---- the tokens of this wave, U at a time
+  for (uint32_t k0 = 0; k0 < passes; k0 += U) {
+    u32x2 code[U];
+    f32x2 sm[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t k = k0 + u < passes ? k0 + u : passes - 1;
+      code[u] = stream_load<u32x2>(fsec + (lane_value(src_tok, k) + src_lane));
+      if (MODE == KVC_Q_PER_TOKEN)
+        sm[u] = *(const KVC_GLOBAL f32x2*)(mrow + (size_t)lane_value(tc, k) * ((uint32_t)g.H * 8u));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t k = k0 + u;
+      if (k >= passes || !((live_mask >> k) & 1ull)) continue;  // wave-uniform
+      const uint64_t off = ((uint64_t)lane_value(dst_hi, k) << 32) | lane_value(dst_lo, k);
+      dequant_store<MODE, DT>(reinterpret_cast<uint16_t*>(obase + off), code[u], sc, mn, sm[u]);
+    }
+  }
+}
+
+// ----------------------------------------------------------------- "lanes" body
+
+template <int MODE, int DT, bool PAGED>
+__device__ __forceinline__ void restore_body_lanes(const RestoreParams& p, uint32_t c, uint32_t kind, uint32_t l,
+                                                   uint32_t tbi) {
+  constexpr int U = KVC_RESTORE_U;
+  const Geo& g = p.g;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t tsub = fd_div(p.dapt, tid);
+  const uint32_t e = (tid - tsub * (uint32_t)g.apt) * 8u;
+
+  const int64_t chunk_first = (int64_t)c * g.T;
+  const int64_t left = p.n_tokens - chunk_first;
+  const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
   const int32_t t0 = (int32_t)tbi * p.tb;
   const int32_t t1 = t0 + p.tb < n ? t0 + p.tb : n;
   if (t0 >= t1) return;
 
-  // intra-frame layout: element e of the token -> (row, column) of its tile
   uint32_t r, cc;
   fd_divmod(g.dtw, e, r, cc);
   const uint32_t lg = l / 3u, pl = l - lg * 3u;
   const uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes +
                          (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane + (r * (uint32_t)g.W + cc);
   const float* mbase = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind];
-
   float sc[8], mn[8];
   const float* mrow = nullptr;
-  if (MODE == KVC_Q_PER_CHANNEL) {
-    const KVC_GLOBAL f32x2* mp = (const KVC_GLOBAL f32x2*)(mbase + 2 * ((int64_t)l * g.C + e));
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const f32x2 v = mp[i];
-      sc[i] = v.x;
-      mn[i] = v.y;
-    }
-  } else {
-    const uint32_t h = fd_div(g.dD, e);
-    mrow = mbase + 2 * ((int64_t)l * g.T * g.H + h);
-  }
-
+  if (MODE == KVC_Q_PER_CHANNEL)
+    load_channel_pairs(mbase, (int64_t)l * g.C + e, sc, mn);
+  else
+    mrow = mbase + 2 * ((int64_t)l * g.T * g.H + fd_div(g.dD, e));
   uint16_t* obase;
-  if (PAGED) {
+  if (PAGED)
     obase = reinterpret_cast<uint16_t*>(as_const(p.layer_cache)[l]) + (int64_t)kind * p.num_blocks * p.dbs.d * g.C + e;
-  } else {
+  else
     obase = p.out + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts + e;
-  }
-  const uint32_t pos0 = (uint32_t)(p.first_token + chunk_first);  // sequence position of the chunk's token 0
+  const uint32_t pos0 = (uint32_t)(p.first_token + chunk_first);
 
   const int32_t step = p.tpp;
   for (int32_t tb0 = t0; tb0 < t1; tb0 += U * step) {
     u32x2 code[U];
     f32x2 sm[U];
     uint16_t* dst[U];
-    bool live[U];      // wave-uniform when the token index is
-    uint32_t slot[U];  // paged: slot inside the block
-    int32_t phys[U];   // paged: physical block id
-    // 1) all streaming loads of the batch are issued before anything waits
+    bool live[U];
+    bool bad = false;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int32_t t = tb0 + u * step + (int32_t)tsub;
       live[u] = t < t1;
-      const uint32_t tc = (uint32_t)(live[u] ? t : t1 - 1);  // clamp: the load stays in bounds, the store is skipped
-      // inter-frame layout: token -> (frame of its group, tile position of its group)
+      const uint32_t tc = (uint32_t)(live[u] ? t : t1 - 1);
       uint32_t gi, f, ty, tx;
       fd_divmod(g.dF, tc, gi, f);
       fd_divmod(g.dTX, gi, ty, tx);
-      const uint8_t* src = fbase + (int64_t)f * 3 * g.plane + ((int64_t)ty * g.th * g.W + tx * (uint32_t)g.tw);
-      code[u] = stream_load<u32x2>(src);
+      code[u] = stream_load<u32x2>(fbase + ((size_t)f * p.frame_stride + ty * p.tile_row_stride + tx * (uint32_t)g.tw));
       if (MODE == KVC_Q_PER_TOKEN) sm[u] = *(const KVC_GLOBAL f32x2*)(mrow + 2 * (int64_t)tc * g.H);
       if (PAGED) {
-        uint32_t b;
-        fd_divmod(p.dbs, pos0 + tc, b, slot[u]);
-        phys[u] = as_const(p.table)[b];
+        uint32_t b, slot;
+        fd_divmod(p.dbs, pos0 + tc, b, slot);
+        const int32_t phys = as_const(p.table)[b];
+        const bool in_cache = (uint32_t)phys < (uint32_t)p.num_blocks;
+        bad = bad || (live[u] && !in_cache);
+        live[u] = live[u] && in_cache;
+        dst[u] = obase + ((int64_t)(in_cache ? phys : 0) * p.dbs.d + slot) * g.C;
       } else {
         dst[u] = obase + (int64_t)tc * p.ts;
       }
     }
-    // 2) placement (Sec. 3.3.2: preallocated slots of the paged memory)
-    if (PAGED) {
-      bool bad = false;
+    if (PAGED && bad && e == 0 && p.err) atomicOr(p.err, 1u);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const bool in_cache = (uint32_t)phys[u] < (uint32_t)p.num_blocks;
-        bad = bad || (live[u] && !in_cache);
-        live[u] = live[u] && in_cache;  // an id outside the cache: skip the block's writes
-        dst[u] = obase + ((int64_t)(in_cache ? phys[u] : 0) * p.dbs.d + slot[u]) * g.C;
-      }
-      if (bad && ca == 0 && p.err) atomicOr(p.err, 1u);  // ... and report it
-    }
-    // 3) dequantize and store
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (!live[u]) continue;
-      float x[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t w = i < 4 ? code[u].x : code[u].y;
-        const float q = (float)((w >> (8 * (i & 3))) & 0xffu);
-        x[i] = MODE == KVC_Q_PER_CHANNEL ? __builtin_fmaf(q, sc[i], mn[i]) : __builtin_fmaf(q, sm[u].x, sm[u].y);
-        // The dequantized value is defined as the binary32 fma result, then rounded
-        // to 16 bits.  Keep the two roundings apart: a mixed-precision fma that
-        // rounds the exact sum straight to fp16 differs in about 1 value in 10^4.
-        asm("" : "+v"(x[i]));
-      }
-      u32x4 o;
-      o.x = narrow_pair<DT>(x[0], x[1]);
-      o.y = narrow_pair<DT>(x[2], x[3]);
-      o.z = narrow_pair<DT>(x[4], x[5]);
-      o.w = narrow_pair<DT>(x[6], x[7]);
-      stream_store<u32x4>(dst[u], o);
-    }
+    for (int u = 0; u < U; ++u)
+      if (live[u]) dequant_store<MODE, DT>(dst[u], code[u], sc, mn, sm[u]);
   }
 }
 
-template <int DT, bool PAGED, bool UNIFORM>
+// Workgroups are handed to the 8 XCDs round-robin.  Each XCD gets one contiguous
+// range of units (unit = token block, fastest, then layer, then kind, then
+// chunk), so the workgroups that share a layer's per-channel pairs and a run of
+// block-table entries also share an L2, and each L2 streams whole frame rows.
+template <int DT, bool PAGED, bool WAVES>
 __global__ void __launch_bounds__(1024) restore_kernel(const RestoreParams p) {
-  // Workgroups are handed to the 8 XCDs round-robin.  Give each XCD one
-  // contiguous range of units so that the workgroups sharing a layer's
-  // per-channel scale/min and block-table entries also share an L2.
+#ifdef KVC_NO_XCD_REMAP
+  const uint32_t unit = blockIdx.x;
+#else
   const uint32_t unit = (blockIdx.x & 7u) * p.units_per_xcd + (blockIdx.x >> 3);
+#endif
   if (unit >= p.n_units) return;
-  uint32_t u = unit;
-  const uint32_t tbi = u % (uint32_t)p.tbc;
-  u /= (uint32_t)p.tbc;
-  const uint32_t l = u % (uint32_t)p.g.L;
-  u /= (uint32_t)p.g.L;
-  const uint32_t kind = u & 1u;
-  const uint32_t c = u >> 1;
-  if (p.g.mode[kind] == KVC_Q_PER_CHANNEL)
-    restore_body<KVC_Q_PER_CHANNEL, DT, PAGED, UNIFORM>(p, c, kind, l, tbi);
-  else
-    restore_body<KVC_Q_PER_TOKEN, DT, PAGED, UNIFORM>(p, c, kind, l, tbi);
+  uint32_t rest, tbi, l;
+  fd_divmod(p.dtbc, unit, rest, tbi);
+  fd_divmod(p.dL, rest, rest, l);
+  const uint32_t kind = rest & 1u, c = rest >> 1;
+  if (p.g.mode[kind] == KVC_Q_PER_CHANNEL) {
+    if (WAVES)
+      restore_body_waves<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi);
+    else
+      restore_body_lanes<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi);
+  } else {
+    if (WAVES)
+      restore_body_waves<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi);
+    else
+      restore_body_lanes<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi);
+  }
 }
 
 template <int DT, bool PAGED>
-void launch_variant(const RestoreParams& p, bool uniform, dim3 grid, dim3 block, hipStream_t s) {
-  if (uniform)
+void launch_variant(const RestoreParams& p, bool waves, dim3 grid, dim3 block, hipStream_t s) {
+  if (waves)
     hipLaunchKernelGGL((restore_kernel<DT, PAGED, true>), grid, block, 0, s, p);
   else
     hipLaunchKernelGGL((restore_kernel<DT, PAGED, false>), grid, block, 0, s, p);
@@ -182,38 +291,56 @@ void launch_variant(const RestoreParams& p, bool uniform, dim3 grid, dim3 block,
 kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream) {
   const Geo& g = p.g;
   if (p.n_tokens <= 0) return KVC_OK;
-  // threads: a whole number of tokens per pass, about 256 threads
   if (g.apt > 1024) return KVC_ERR_UNSUPPORTED;
-  const int tpp = g.apt >= 256 ? 1 : 256 / g.apt;
+  // threads: a whole number of tokens per pass, about 256 threads
+#ifndef KVC_RESTORE_THREADS
+#define KVC_RESTORE_THREADS 512
+#endif
+  const int tpp = g.apt >= KVC_RESTORE_THREADS ? 1 : KVC_RESTORE_THREADS / g.apt;
   const int threads = g.apt * tpp;
+  const bool waves = g.apt % 64 == 0;
   p.tpp = tpp;
   p.dapt = make_fastdiv((uint32_t)g.apt);
-  if (p.tb <= 0) {
-#ifdef KVC_RESTORE_TB
-    p.tb = KVC_RESTORE_TB;
-#else
-    p.tb = 128;
-#endif
-  }
+  p.dwpt = make_fastdiv((uint32_t)(waves ? g.apt / 64 : 1));
+  if (g.frame_bytes >= (1ll << 32)) return KVC_ERR_UNSUPPORTED;  // offsets inside a chunk section are 32-bit
+  p.frame_stride = (uint32_t)(3 * g.plane);
+  p.tile_row_stride = (uint32_t)g.th * (uint32_t)g.W;
+  if (p.tb <= 0) p.tb = waves ? KVC_RESTORE_TB : KVC_RESTORE_TB_LANES;
+  if (waves && p.tb > 64 * tpp) p.tb = 64 * tpp;  // one lane per token of a wave
   if (p.tb > g.T) p.tb = g.T;
   p.tbc = (g.T + p.tb - 1) / p.tb;
+  p.tstart = p.tb;
+  p.tstride = tpp;
+#ifdef KVC_RESTORE_NW
+  if (waves && KVC_RESTORE_NW > 0) {
+    // interleaved: nw workgroups per (chunk, kind, layer), at most 64 passes each
+    int nw = KVC_RESTORE_NW;
+    const int passes_total = (g.T + tpp - 1) / tpp;
+    if (nw > passes_total) nw = passes_total;
+    if ((passes_total + nw - 1) / nw > 64) nw = (passes_total + 63) / 64;
+    p.tbc = nw;
+    p.tstart = tpp;
+    p.tstride = tpp * nw;
+  }
+#endif
   p.n_chunks = (int32_t)((p.n_tokens + g.T - 1) / g.T);
   const int64_t units = (int64_t)p.n_chunks * 2 * g.L * p.tbc;
   if (units > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
   p.n_units = (uint32_t)units;
   p.units_per_xcd = (p.n_units + 7u) / 8u;
+  p.dtbc = make_fastdiv((uint32_t)p.tbc);
+  p.dL = make_fastdiv((uint32_t)g.L);
   const dim3 grid(p.units_per_xcd * 8u), block((unsigned)threads);
-  const bool uniform = g.apt % 64 == 0;
   if (g.dtype == KVC_F16) {
     if (paged)
-      launch_variant<KVC_F16, true>(p, uniform, grid, block, stream);
+      launch_variant<KVC_F16, true>(p, waves, grid, block, stream);
     else
-      launch_variant<KVC_F16, false>(p, uniform, grid, block, stream);
+      launch_variant<KVC_F16, false>(p, waves, grid, block, stream);
   } else {
     if (paged)
-      launch_variant<KVC_BF16, true>(p, uniform, grid, block, stream);
+      launch_variant<KVC_BF16, true>(p, waves, grid, block, stream);
     else
-      launch_variant<KVC_BF16, false>(p, uniform, grid, block, stream);
+      launch_variant<KVC_BF16, false>(p, waves, grid, block, stream);
   }
   return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_RUNTIME;
 }
