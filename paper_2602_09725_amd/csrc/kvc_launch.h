@@ -58,6 +58,7 @@ struct PackParams {
   int32_t n_strips;
   int32_t rows;           // token rows per pass = threads / strip_atoms
   int32_t n_kinds_ch;
+  int32_t resident;       // per-channel strips are held in registers (one read of the input)
   int32_t kinds_ch[2];
   // work units of the two kinds of workgroup and their share per XCD
   uint32_t n_units_ch, n_units_tok;

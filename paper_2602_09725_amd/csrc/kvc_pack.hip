@@ -48,13 +48,35 @@ __device__ __forceinline__ GroupParams group_params(float lo, float hi) {
   return q;
 }
 
-// code = clamp(rint((x - mn) * inv), 0, 255); subtraction and product are
-// separately rounded (no contraction is possible: there is no add after the mul).
-__device__ __forceinline__ uint32_t quantize(float x, float mn, float inv) {
-  const float pos = (x - mn) * inv;
-  float q = __builtin_rintf(pos);
-  q = __builtin_fminf(__builtin_fmaxf(q, 0.0f), 255.0f);
-  return (uint32_t)q;
+// code = clamp(rint((x - mn) * inv), 0, 255), written into byte `sel` of `acc`.
+// Subtraction and product are separately rounded (no contraction is possible:
+// there is no add after the mul).  v_cvt_pk_u8_f32 rounds to nearest even under
+// the default rounding mode and saturates to [0, 255], i.e. it is rint + clamp +
+// convert + byte insert in one instruction.
+__device__ __forceinline__ uint32_t quantize_into(uint32_t acc, uint32_t sel, float x, float mn, float inv) {
+  return __builtin_amdgcn_cvt_pk_u8_f32((x - mn) * inv, sel, acc);
+}
+
+// 8 elements -> 8 code bytes with one {mn, inv} for all (per-token groups)
+__device__ __forceinline__ u32x2 quantize_atom(const float (&x)[8], float mn, float inv) {
+  u32x2 o{0u, 0u};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    o.x = quantize_into(o.x, i, x[i], mn, inv);
+    o.y = quantize_into(o.y, i, x[4 + i], mn, inv);
+  }
+  return o;
+}
+
+// 8 elements -> 8 code bytes with one {mn, inv} per element (per-channel groups)
+__device__ __forceinline__ u32x2 quantize_atom(const float (&x)[8], const float (&mn)[8], const float (&inv)[8]) {
+  u32x2 o{0u, 0u};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    o.x = quantize_into(o.x, i, x[i], mn[i], inv[i]);
+    o.y = quantize_into(o.y, i, x[4 + i], mn[4 + i], inv[4 + i]);
+  }
+  return o;
 }
 
 template <int DT>
@@ -65,9 +87,108 @@ __device__ __forceinline__ void widen_atom(const u32x4& v, float (&x)[8]) {
   widen_pair<DT>(v.w, x[6], x[7]);
 }
 
-__device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
-  return a | (b << 8) | (c << 16) | (d << 24);
+// Minimum and maximum of the 8 elements of an atom.  fp16 pairs are compared with
+// the packed half-precision min / max (exact), two elements per instruction.
+template <int DT>
+__device__ __forceinline__ void atom_minmax(const u32x4& v, float& lo, float& hi);
+template <>
+__device__ __forceinline__ void atom_minmax<KVC_F16>(const u32x4& v, float& lo, float& hi) {
+  // (copy the components to scalars first: a bit cast applied directly to a
+  // component of a vector reads the wrong dword with this compiler)
+  const uint32_t w0 = v.x, w1 = v.y, w2 = v.z, w3 = v.w;
+  const f16x2 a = __builtin_bit_cast(f16x2, w0), b = __builtin_bit_cast(f16x2, w1);
+  const f16x2 c = __builtin_bit_cast(f16x2, w2), d = __builtin_bit_cast(f16x2, w3);
+  const f16x2 mn = __builtin_elementwise_min(__builtin_elementwise_min(a, b), __builtin_elementwise_min(c, d));
+  const f16x2 mx = __builtin_elementwise_max(__builtin_elementwise_max(a, b), __builtin_elementwise_max(c, d));
+  lo = __builtin_fminf((float)mn.x, (float)mn.y);
+  hi = __builtin_fmaxf((float)mx.x, (float)mx.y);
 }
+template <>
+__device__ __forceinline__ void atom_minmax<KVC_BF16>(const u32x4& v, float& lo, float& hi) {
+  float x[8];
+  widen_atom<KVC_BF16>(v, x);
+  lo = hi = x[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i) {
+    lo = __builtin_fminf(lo, x[i]);
+    hi = __builtin_fmaxf(hi, x[i]);
+  }
+}
+
+// Running per-channel minimum / maximum of the 8 channels of an atom over many
+// tokens.  fp16 stays packed (4 + 4 VGPRs, two channels per instruction); bf16
+// is widened first (no packed bf16 compare).
+template <int DT>
+struct ColumnStats;
+template <>
+struct ColumnStats<KVC_F16> {
+  f16x2 lo[4], hi[4];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      lo[j] = f16x2{(_Float16)__builtin_inff(), (_Float16)__builtin_inff()};
+      hi[j] = f16x2{(_Float16)-__builtin_inff(), (_Float16)-__builtin_inff()};
+    }
+  }
+  __device__ __forceinline__ void add(const u32x4& v) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      lo[j] = __builtin_elementwise_min(lo[j], __builtin_bit_cast(f16x2, w[j]));
+      hi[j] = __builtin_elementwise_max(hi[j], __builtin_bit_cast(f16x2, w[j]));
+    }
+  }
+  __device__ __forceinline__ void merge_xor(int m) {  // with the lane m away
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      lo[j] = __builtin_elementwise_min(lo[j], __builtin_bit_cast(f16x2, __shfl_xor(__builtin_bit_cast(uint32_t, lo[j]), m)));
+      hi[j] = __builtin_elementwise_max(hi[j], __builtin_bit_cast(f16x2, __shfl_xor(__builtin_bit_cast(uint32_t, hi[j]), m)));
+    }
+  }
+  __device__ __forceinline__ void get(float (&l)[8], float (&h)[8]) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      l[2 * j] = (float)lo[j].x;
+      l[2 * j + 1] = (float)lo[j].y;
+      h[2 * j] = (float)hi[j].x;
+      h[2 * j + 1] = (float)hi[j].y;
+    }
+  }
+};
+template <>
+struct ColumnStats<KVC_BF16> {
+  float lo[8], hi[8];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      lo[j] = __builtin_inff();
+      hi[j] = -__builtin_inff();
+    }
+  }
+  __device__ __forceinline__ void add(const u32x4& v) {
+    float x[8];
+    widen_atom<KVC_BF16>(v, x);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      lo[j] = __builtin_fminf(lo[j], x[j]);
+      hi[j] = __builtin_fmaxf(hi[j], x[j]);
+    }
+  }
+  __device__ __forceinline__ void merge_xor(int m) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      lo[j] = __builtin_fminf(lo[j], __shfl_xor(lo[j], m));
+      hi[j] = __builtin_fmaxf(hi[j], __shfl_xor(hi[j], m));
+    }
+  }
+  __device__ __forceinline__ void get(float (&l)[8], float (&h)[8]) const {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      l[j] = lo[j];
+      h[j] = hi[j];
+    }
+  }
+};
 
 // Address of the 8 code bytes of atom (row r, column cc already folded into
 // fbase) of token position t inside the (chunk, kind, layer) plane sequence.
@@ -137,24 +258,16 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
         if (leader && t < g.T && l < (uint32_t)g.L) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{0.f, 0.f};
         continue;
       }
-      float x[8];
-      widen_atom<DT>(v[u], x);
-      float lo = x[0], hi = x[0];
-#pragma unroll
-      for (int i = 1; i < 8; ++i) {
-        lo = __builtin_fminf(lo, x[i]);
-        hi = __builtin_fmaxf(hi, x[i]);
-      }
+      float lo, hi;
+      atom_minmax<DT>(v[u], lo, hi);
       for (uint32_t m = 1; m < glanes; m <<= 1) {  // butterfly over the lanes of the head
         lo = __builtin_fminf(lo, __shfl_xor(lo, (int)m));
         hi = __builtin_fmaxf(hi, __shfl_xor(hi, (int)m));
       }
       const GroupParams q = group_params(lo, hi);
-      u32x2 o;
-      o.x = pack4(quantize(x[0], q.mn, q.inv), quantize(x[1], q.mn, q.inv), quantize(x[2], q.mn, q.inv),
-                  quantize(x[3], q.mn, q.inv));
-      o.y = pack4(quantize(x[4], q.mn, q.inv), quantize(x[5], q.mn, q.inv), quantize(x[6], q.mn, q.inv),
-                  quantize(x[7], q.mn, q.inv));
+      float x[8];
+      widen_atom<DT>(v[u], x);
+      const u32x2 o = quantize_atom(x, q.mn, q.inv);
       stream_store<u32x2>(dst, o);
       if (leader) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{q.scale, q.mn};
     }
@@ -210,12 +323,8 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
 
   if (n > 0) {
     // pass 1: column min / max of the strip over the chunk's valid tokens
-    float lo[8], hi[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      lo[i] = __builtin_inff();
-      hi[i] = -__builtin_inff();
-    }
+    ColumnStats<DT> st;
+    st.init();
     for (uint32_t tb0 = 0; tb0 < (uint32_t)n; tb0 += U * rows) {
       u32x4 v[U];
 #pragma unroll
@@ -225,24 +334,12 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
         v[u] = *reinterpret_cast<const u32x4*>(src + (int64_t)tc * p.ts);  // cached: read again in pass 2
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        float x[8];
-        widen_atom<DT>(v[u], x);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          lo[i] = __builtin_fminf(lo[i], x[i]);
-          hi[i] = __builtin_fmaxf(hi[i], x[i]);
-        }
-      }
+      for (int u = 0; u < U; ++u) st.add(v[u]);
     }
     // lanes holding the same atom differ by multiples of sa
-    for (uint32_t m = sa; m < 64u; m <<= 1) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        lo[i] = __builtin_fminf(lo[i], __shfl_xor(lo[i], (int)m));
-        hi[i] = __builtin_fmaxf(hi[i], __shfl_xor(hi[i], (int)m));
-      }
-    }
+    for (uint32_t m = sa; m < 64u; m <<= 1) st.merge_xor((int)m);
+    float lo[8], hi[8];
+    st.get(lo, hi);
     const uint32_t wave = tid >> 6, lane = tid & 63u;
     const uint32_t n_waves = blockDim.x >> 6;
     if (lane < sa) {
@@ -287,17 +384,121 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
       if (t < (uint32_t)n) {
         float x[8];
         widen_atom<DT>(v[u], x);
-        o.x = pack4(quantize(x[0], mnv[0], inv[0]), quantize(x[1], mnv[1], inv[1]), quantize(x[2], mnv[2], inv[2]),
-                    quantize(x[3], mnv[3], inv[3]));
-        o.y = pack4(quantize(x[4], mnv[4], inv[4]), quantize(x[5], mnv[5], inv[5]), quantize(x[6], mnv[6], inv[6]),
-                    quantize(x[7], mnv[7], inv[7]));
+        o = quantize_atom(x, mnv, inv);
       }
       stream_store<u32x2>(code_addr(g, fbase, t), o);
     }
   }
 }
 
-template <int DT, bool UNIFORM>
+// Register-resident variant: the strip of one (chunk, kind, layer) -- up to
+// kResidentLoads * rows tokens x 64 channels, 256 KB of fp16 at 1024 threads --
+// is loaded once into VGPRs (64 per thread), reduced, and quantized from the
+// registers, so the input is read from HBM exactly once.  The CDNA register file
+// (512 KB per CU) is what makes this possible; LDS (160 KB) could not hold it.
+constexpr int kResidentLoads = 16;
+
+template <int DT>
+__device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, uint32_t unit,
+                                                           float (*red_lo)[kMaxStripAtoms * 8],
+                                                           float (*red_hi)[kMaxStripAtoms * 8]) {
+  constexpr int NI = kResidentLoads;
+  const Geo& g = p.g;
+  uint32_t uu = unit;
+  const uint32_t strip = uu % (uint32_t)p.n_strips;
+  uu /= (uint32_t)p.n_strips;
+  const uint32_t l3 = (uint32_t)(3 * g.LG);
+  const uint32_t l = uu % l3;
+  uu /= l3;
+  const uint32_t kind = (uint32_t)p.kinds_ch[uu % (uint32_t)p.n_kinds_ch];
+  const uint32_t c = uu / (uint32_t)p.n_kinds_ch;
+
+  const uint32_t tid = threadIdx.x;
+  const uint32_t sa = (uint32_t)p.strip_atoms;
+  const uint32_t a = tid & (sa - 1u);
+  const uint32_t row = tid / sa;
+  const uint32_t rows = (uint32_t)p.rows;
+  const uint32_t ca = strip * sa + a;
+  const bool active = ca < (uint32_t)g.apt;
+  const uint32_t e = (active ? ca : 0u) * 8u;
+
+  const int64_t chunk_first = (int64_t)c * g.T;
+  const int64_t left = p.n_tokens - chunk_first;
+  int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
+  if (l >= (uint32_t)g.L) n = 0;
+
+  uint32_t r, cc;
+  fd_divmod(g.dtw, e, r, cc);
+  const uint32_t lg = l / 3u, pl = l - lg * 3u;
+  uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane +
+                   (r * (uint32_t)g.W + cc);
+  const uint16_t* src = p.kv + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts + e;
+
+  u32x4 v[NI];
+  float mnv[8], inv[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) mnv[i] = inv[i] = 0.f;
+
+  if (n > 0) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const uint32_t t = row + (uint32_t)i * rows;
+      const uint32_t tc = t < (uint32_t)n ? t : (uint32_t)n - 1u;  // a repeated token leaves min / max unchanged
+      v[i] = stream_load<u32x4>(src + (int64_t)tc * p.ts);
+    }
+    ColumnStats<DT> st;
+    st.init();
+#pragma unroll
+    for (int i = 0; i < NI; ++i) st.add(v[i]);
+    for (uint32_t m = sa; m < 64u; m <<= 1) st.merge_xor((int)m);
+    float lo[8], hi[8];
+    st.get(lo, hi);
+    const uint32_t wave = tid >> 6, lane = tid & 63u;
+    const uint32_t n_waves = blockDim.x >> 6;
+    if (lane < sa) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        red_lo[wave][lane * 8 + i] = lo[i];
+        red_hi[wave][lane * 8 + i] = hi[i];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float l0 = red_lo[0][a * 8 + i], h0 = red_hi[0][a * 8 + i];
+      for (uint32_t w = 1; w < n_waves; ++w) {
+        l0 = __builtin_fminf(l0, red_lo[w][a * 8 + i]);
+        h0 = __builtin_fmaxf(h0, red_hi[w][a * 8 + i]);
+      }
+      const GroupParams q = group_params(l0, h0);
+      mnv[i] = q.mn;
+      inv[i] = q.inv;
+      if (row == 0 && active) {
+        float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + e + i);
+        *reinterpret_cast<f32x2*>(mp) = f32x2{q.scale, q.mn};
+      }
+    }
+  }
+  if (!active) return;  // after the barrier: lanes of a ragged last strip store nothing
+
+  // quantize from the registers; tile positions without a token get zeros
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const uint32_t t = row + (uint32_t)i * rows;
+    if (t >= (uint32_t)g.FG) continue;
+    u32x2 o{0u, 0u};
+    if (t < (uint32_t)n) {
+      float x[8];
+      widen_atom<DT>(v[i], x);
+      o = quantize_atom(x, mnv, inv);
+    }
+    stream_store<u32x2>(code_addr(g, fbase, t), o);
+  }
+  for (uint32_t t = row + (uint32_t)NI * rows; t < (uint32_t)g.FG; t += rows)
+    stream_store<u32x2>(code_addr(g, fbase, t), u32x2{0u, 0u});
+}
+
+template <int DT, bool UNIFORM, bool RESIDENT>
 __global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
   __shared__ float red_lo[kMaxWaves][kMaxStripAtoms * 8];
   __shared__ float red_hi[kMaxWaves][kMaxStripAtoms * 8];
@@ -307,7 +508,12 @@ __global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
   const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
   if (idx < p.ch_per_xcd) {
     const uint32_t unit = xcd * p.ch_per_xcd + idx;
-    if (unit < p.n_units_ch) pack_channel_body<DT>(p, unit, red_lo, red_hi);
+    if (unit < p.n_units_ch) {
+      if (RESIDENT)
+        pack_channel_body_resident<DT>(p, unit, red_lo, red_hi);
+      else
+        pack_channel_body<DT>(p, unit, red_lo, red_hi);
+    }
   } else {
     const uint32_t unit = xcd * p.tok_per_xcd + (idx - p.ch_per_xcd);
     if (unit < p.n_units_tok) pack_token_body<DT, UNIFORM>(p, unit);
@@ -331,9 +537,16 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
   // per-token part: a whole number of tokens per pass, about 256 threads
   const int glanes = g.D / 8;
   if (p.n_kinds_tok > 0 && (glanes > 64 || (glanes & (glanes - 1)) != 0)) return KVC_ERR_UNSUPPORTED;
-  p.tpp = g.apt >= 256 ? 1 : 256 / g.apt;
+  // Per-channel kinds whose chunk fits the register-resident strip run with 1024
+  // threads (the strip then spans 128 token rows x 16 loads = 2048 tokens).
+#ifndef KVC_PACK_RESIDENT
+#define KVC_PACK_RESIDENT 1
+#endif
+  p.resident = KVC_PACK_RESIDENT && p.n_kinds_ch > 0 && g.T <= kResidentLoads * (1024 / 8) ? 1 : 0;
+  const int want = p.resident ? 1024 : 256;
+  p.tpp = g.apt >= want ? 1 : want / g.apt;
   p.dapt = make_fastdiv((uint32_t)g.apt);
-  const int threads = (g.apt * p.tpp + 63) / 64 * 64;
+  const int threads = p.resident ? 1024 : (g.apt * p.tpp + 63) / 64 * 64;
 #ifdef KVC_PACK_TB
   p.tb = KVC_PACK_TB;
 #else
@@ -359,17 +572,21 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
   p.units_per_xcd = p.ch_per_xcd + p.tok_per_xcd;
   const dim3 grid(p.units_per_xcd * 8u), block((unsigned)threads);
   const bool uniform = g.apt % 64 == 0;
+#define KVC_LAUNCH_PACK(DT_, UNI_, RES_) hipLaunchKernelGGL((pack_kernel<DT_, UNI_, RES_>), grid, block, 0, stream, p)
   if (g.dtype == KVC_F16) {
-    if (uniform)
-      hipLaunchKernelGGL((pack_kernel<KVC_F16, true>), grid, block, 0, stream, p);
-    else
-      hipLaunchKernelGGL((pack_kernel<KVC_F16, false>), grid, block, 0, stream, p);
+    if (uniform) {
+      if (p.resident) KVC_LAUNCH_PACK(KVC_F16, true, true); else KVC_LAUNCH_PACK(KVC_F16, true, false);
+    } else {
+      if (p.resident) KVC_LAUNCH_PACK(KVC_F16, false, true); else KVC_LAUNCH_PACK(KVC_F16, false, false);
+    }
   } else {
-    if (uniform)
-      hipLaunchKernelGGL((pack_kernel<KVC_BF16, true>), grid, block, 0, stream, p);
-    else
-      hipLaunchKernelGGL((pack_kernel<KVC_BF16, false>), grid, block, 0, stream, p);
+    if (uniform) {
+      if (p.resident) KVC_LAUNCH_PACK(KVC_BF16, true, true); else KVC_LAUNCH_PACK(KVC_BF16, true, false);
+    } else {
+      if (p.resident) KVC_LAUNCH_PACK(KVC_BF16, false, true); else KVC_LAUNCH_PACK(KVC_BF16, false, false);
+    }
   }
+#undef KVC_LAUNCH_PACK
   return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_RUNTIME;
 }
 
