@@ -542,23 +542,26 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
 #ifndef KVC_PACK_RESIDENT
 #define KVC_PACK_RESIDENT 1
 #endif
-  p.resident = KVC_PACK_RESIDENT && p.n_kinds_ch > 0 && g.T <= kResidentLoads * (1024 / 8) ? 1 : 0;
-  const int want = p.resident ? 1024 : 256;
-  p.tpp = g.apt >= want ? 1 : want / g.apt;
-  p.dapt = make_fastdiv((uint32_t)g.apt);
-  const int threads = p.resident ? 1024 : (g.apt * p.tpp + 63) / 64 * 64;
-#ifdef KVC_PACK_TB
-  p.tb = KVC_PACK_TB;
-#else
-  p.tb = 64;
+#ifndef KVC_PACK_RES_THREADS
+#define KVC_PACK_RES_THREADS 1024
 #endif
-  p.tbc = (g.FG + p.tb - 1) / p.tb;
-  // per-channel part: strips of 8*strip_atoms channels
 #ifdef KVC_PACK_STRIP_ATOMS
   p.strip_atoms = KVC_PACK_STRIP_ATOMS;
 #else
   p.strip_atoms = 8;  // 64 channels: 128-byte input rows, 64-byte code rows
 #endif
+  p.resident = KVC_PACK_RESIDENT && p.n_kinds_ch > 0 && g.T <= kResidentLoads * (KVC_PACK_RES_THREADS / p.strip_atoms) ? 1 : 0;
+  const int want = p.resident ? KVC_PACK_RES_THREADS : 256;
+  p.tpp = g.apt >= want ? 1 : want / g.apt;
+  p.dapt = make_fastdiv((uint32_t)g.apt);
+  const int threads = p.resident ? KVC_PACK_RES_THREADS : (g.apt * p.tpp + 63) / 64 * 64;
+#ifdef KVC_PACK_TB
+  p.tb = KVC_PACK_TB;
+#else
+  p.tb = 256;
+#endif
+  p.tbc = (g.FG + p.tb - 1) / p.tb;
+  // per-channel part: strips of 8*strip_atoms channels
   p.n_strips = (g.apt + p.strip_atoms - 1) / p.strip_atoms;
   p.rows = threads / p.strip_atoms;
   const int64_t per_kind = (int64_t)p.n_chunks * 3 * g.LG;
