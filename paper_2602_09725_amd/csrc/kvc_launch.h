@@ -16,8 +16,6 @@ struct RestoreParams {
   int32_t tb;             // tokens per workgroup (0: library default)
   int32_t tbc;            // token blocks per chunk
   int32_t tpp;            // tokens per pass of a workgroup = threads / apt
-  int32_t tstart;         // first token of workgroup i of a chunk = i * tstart
-  int32_t tstride;        // tokens between consecutive passes of a workgroup
   uint32_t n_units;       // n_chunks * 2 * L * tbc workgroups with work
   uint32_t units_per_xcd;
   FastDiv dtbc, dL;       // unit -> (token block, layer, kind, chunk)

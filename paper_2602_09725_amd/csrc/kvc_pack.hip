@@ -550,7 +550,10 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
 #else
   p.strip_atoms = 8;  // 64 channels: 128-byte input rows, 64-byte code rows
 #endif
-  p.resident = KVC_PACK_RESIDENT && p.n_kinds_ch > 0 && g.T <= kResidentLoads * (KVC_PACK_RES_THREADS / p.strip_atoms) ? 1 : 0;
+  p.resident = KVC_PACK_RESIDENT && p.n_kinds_ch > 0 && g.T <= kResidentLoads * (KVC_PACK_RES_THREADS / p.strip_atoms) &&
+                       (int64_t)g.T * p.ts * 2 < (1ll << 32) && g.frame_bytes < (1ll << 32)
+                   ? 1
+                   : 0;
   const int want = p.resident ? KVC_PACK_RES_THREADS : 256;
   p.tpp = g.apt >= want ? 1 : want / g.apt;
   p.dapt = make_fastdiv((uint32_t)g.apt);

@@ -101,17 +101,13 @@ __device__ __forceinline__ void restore_body_waves(const RestoreParams& p, uint3
   const int64_t chunk_first = (int64_t)c * g.T;
   const int64_t left = p.n_tokens - chunk_first;
   const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;  // valid tokens of this chunk
-  // Tokens of this workgroup: passes k = 0, 1, ... take tokens t0 + k * tstride (+ tsub),
-  // up to t1.  Blocked: one run of tb tokens.  Interleaved: the workgroups of a
-  // (chunk, kind, layer) sweep it together, each taking every nw-th pass.
-  const int32_t t0 = (int32_t)tbi * p.tstart;
-  const int32_t t1 = p.tstride == p.tpp ? (t0 + p.tb < n ? t0 + p.tb : n) : n;
+  // Tokens of this workgroup: tb consecutive tokens; pass k of this wave takes token t0 + tsub + k * tpp.
+  const int32_t t0 = (int32_t)tbi * p.tb;
+  const int32_t t1 = t0 + p.tb < n ? t0 + p.tb : n;
   if (t0 >= t1) return;
-
-  // ---- per-token values, one token per lane
-  const int32_t t = t0 + (int32_t)tsub + (int32_t)lane * p.tstride;
+  const int32_t t = t0 + (int32_t)tsub + (int32_t)lane * p.tpp;
   const bool in_range = t < t1;
-  const uint32_t tc = (uint32_t)(in_range ? t : t1 - 1);  // clamp: loads of dead passes stay in bounds
+  const uint32_t tc = (uint32_t)(in_range ? t : t0);  // clamp: loads of dead passes stay in bounds
   // inter-frame layout: token -> (frame of its group, tile position of its group)
   uint32_t gi, f, ty, tx;
   fd_divmod(g.dF, tc, gi, f);
@@ -309,20 +305,6 @@ kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream) {
   if (waves && p.tb > 64 * tpp) p.tb = 64 * tpp;  // one lane per token of a wave
   if (p.tb > g.T) p.tb = g.T;
   p.tbc = (g.T + p.tb - 1) / p.tb;
-  p.tstart = p.tb;
-  p.tstride = tpp;
-#ifdef KVC_RESTORE_NW
-  if (waves && KVC_RESTORE_NW > 0) {
-    // interleaved: nw workgroups per (chunk, kind, layer), at most 64 passes each
-    int nw = KVC_RESTORE_NW;
-    const int passes_total = (g.T + tpp - 1) / tpp;
-    if (nw > passes_total) nw = passes_total;
-    if ((passes_total + nw - 1) / nw > 64) nw = (passes_total + 63) / 64;
-    p.tbc = nw;
-    p.tstart = tpp;
-    p.tstride = tpp * nw;
-  }
-#endif
   p.n_chunks = (int32_t)((p.n_tokens + g.T - 1) / g.T);
   const int64_t units = (int64_t)p.n_chunks * 2 * g.L * p.tbc;
   if (units > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
