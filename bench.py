@@ -12,6 +12,7 @@ every input already resident in HBM.  Prints ONE JSON line.
   cpu_baseline : the CPU oracle on a bounded sample of the same workload
   fetch     : the two-stream pipelined fetch of the same frames from pinned host
               memory (bound by the host link, never part of `value`)
+  fetch_frames : that fetch at frame granularity, with frame-sized staging
 """
 import argparse
 import json
@@ -207,6 +208,31 @@ def main():
                         "bare_h2d_ms": round(min(bare), 3),
                         "h2d_GBps": round(total / (min(bare) * 1e-3) / 1e9, 2),
                         "pcie_inclusive_restore_GBps": round(restore_bytes / (min(times[1:]) * 1e-3) / 1e9, 1)}
+        # the same fetch frame by frame (Sec. 3.3.2): frame-sized staging slots instead of whole chunks
+        fsz = kvc.frame_size(lo)
+        legs = []
+        for order, per_slot, n_fs, n_ms in ((kvc.KVC_ORDER_CHUNK, 1, 6, 2), (kvc.KVC_ORDER_CHUNK, 16, 3, 2),
+                                            (kvc.KVC_ORDER_LAYER, 8, 4, 4), (kvc.KVC_ORDER_LAYER, 32, 3, 8)):
+            msz = kvc.meta_staging_size(lo, order)
+            fstage = [torch.empty(per_slot * fsz, dtype=torch.uint8, device=dev) for _ in range(n_fs)]
+            mstage = [torch.empty(msz, dtype=torch.uint8, device=dev) for _ in range(n_ms)]
+            runs = []
+            for _ in range(4):
+                runs.append(kvc.kvc_fetch_pipeline_frames(lo, chunks, [s.data_ptr() for s in fstage], per_slot * fsz,
+                                                          [s.data_ptr() for s in mstage], msz, ptrs.data_ptr(),
+                                                          n_logical, bs, table.data_ptr(), n_logical, err.data_ptr(),
+                                                          s_copy.cuda_stream, s_comp.cuda_stream, order=order,
+                                                          timed=True, group_times=True))
+                torch.cuda.synchronize()
+            ms_best, groups = min(runs[1:], key=lambda r: r[0])
+            legs.append({"order": "layer" if order == kvc.KVC_ORDER_LAYER else "chunk", "frames_per_slot": per_slot,
+                         "n_frame_staging": n_fs, "n_meta_staging": n_ms,
+                         "staging_MiB": round((n_fs * per_slot * fsz + n_ms * msz) / 2**20, 1),
+                         "fetch_to_ready_ms": round(ms_best, 3),
+                         "first_layer_group_ready_ms": round(groups[0], 3)})
+            del fstage, mstage
+        out["fetch_frames"] = {"frame_bytes": fsz, "frames": len(blobs) * (fb // fsz),
+                               "chunk_staging_MiB": round(n_staging * blob_bytes / 2**20, 1), "legs": legs}
         del blobs, staging
 
     # ---- the CPU oracle on a bounded sample of the same workload (rank 0, N = 1)

@@ -30,8 +30,8 @@
  * G = TX*TY tile positions, F = ceil(T / G) frames per layer group,
  * LG = ceil(L / 3) layer groups, W = TX*tw, Hp = TY*th.
  *
- * Quantizer (the paper only says "quantized to integers", Sec. 4 item (1); the
- * 8-bit asymmetric affine form is this library's definition), all in fp32:
+ * Quantizer (Sec. 4 item (1) states only that the tensors become integers
+ * before encoding; the 8-bit asymmetric affine form is this library's definition), all in fp32:
  *   group  : KVC_Q_PER_CHANNEL -> one (chunk, kind, layer, head, dim) over the
  *            chunk's valid tokens; KVC_Q_PER_TOKEN -> one (kind, layer, token,
  *            head) over the D elements of the head
@@ -160,9 +160,9 @@ kvc_status kvc_pack(const kvc_layout* layout, const void* kv, kvc_strides stride
 kvc_status kvc_restore(const kvc_layout* layout, const uint8_t* frames, const void* meta,
                        int64_t n_tokens, void* kv_out, kvc_strides strides, void* stream);
 
-/* Fetch side into the engine's paged memory (Sec. 3.3.2: "filled into the
- * preallocated slots in the paged memory"; Sec. 4 item (2): the sparse
- * frame-to-paged-memory transfer operator).
+/* Fetch side into the engine's paged memory (Sec. 3.3.2: restored tensors go
+ * straight to slots the engine has already allocated in its paged memory;
+ * Sec. 4 item (2): the sparse frame-to-paged-memory transfer operator).
  *   frames, meta   DEVICE in : sections of the chunks that hold sequence
  *                  positions [first_token, first_token + n_tokens)
  *   first_token    absolute position of token 0 of `frames`; multiple of T
@@ -181,7 +181,7 @@ kvc_status kvc_restore_paged(const kvc_layout* layout, const uint8_t* frames, co
                              int64_t table_len, uint32_t* d_err, void* stream);
 
 /* Pipelined fetcher (Sec. 3.3.2: transmission overlapped with decoding, the
- * restoration riding along; Sec. 3.3.2 "bitstream buffer in host memory").
+ * restoration riding along; the compressed data waits in a host-memory buffer).
  * Chunk i (holding sequence positions i*T ...) is copied from its pinned HOST
  * blob to staging slot i % n_staging on `copy_stream`, then restored into the
  * paged cache on `compute_stream`; a slot is reused only after the restore that
@@ -201,6 +201,103 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
                               void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
                               const int32_t* d_block_table, int64_t table_len, uint32_t* d_err,
                               void* copy_stream, void* compute_stream, float* fetch_to_ready_ms);
+
+/* Frame-wise restoration (Sec. 3.3.2: a frame is mapped back to KV tensors and
+ * placed into the preallocated paged slots as soon as it is available, so the
+ * decompress buffer holds frames, not chunks).
+ * Frames of a chunk are numbered in storage order,
+ *   frame number = (kind * LG + layer_group) * F + frame_index;
+ * one frame = the three planes [3][Hp][W] and carries, for the layers
+ * 3*layer_group .. +2 that exist, the tokens t of the chunk with
+ * t % F == frame_index (Sec. 3.2.1 step 3).
+ *   frames       DEVICE in : n_frames consecutive frames, n_frames*3*Hp*W bytes,
+ *                as they sit in the chunk section from byte
+ *                first_frame * kvc_frame_size(layout) on; 8-byte aligned
+ *   meta         DEVICE in : the meta section of the chunk the frames belong to
+ *   first_frame, n_frames : 0 <= first_frame, n_frames >= 1,
+ *                first_frame + n_frames <= 2*LG*F
+ *   first_token  absolute position of the chunk's token 0 (multiple of T)
+ *   n_tokens     valid tokens of that chunk, 1..T
+ * Destination and error behaviour as kvc_restore_paged.  Restoring every frame of
+ * a chunk, in any order and any grouping, gives the same cache as one
+ * kvc_restore_paged call on the chunk. */
+kvc_status kvc_restore_paged_frames(const kvc_layout* layout, const uint8_t* frames, const void* meta,
+                                    int64_t first_frame, int64_t n_frames, int64_t first_token, int64_t n_tokens,
+                                    void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
+                                    const int32_t* d_block_table, int64_t table_len, uint32_t* d_err, void* stream);
+
+/* The same for the single frame (kind, layer_group, frame_index). */
+kvc_status kvc_restore_paged_frame(const kvc_layout* layout, const uint8_t* frame, const void* meta, int32_t kind,
+                                   int32_t layer_group, int32_t frame_index, int64_t first_token, int64_t n_tokens,
+                                   void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
+                                   const int32_t* d_block_table, int64_t table_len, uint32_t* d_err, void* stream);
+
+/* Bytes of one frame (3*Hp*W) and the offset of frame (kind, layer_group,
+ * frame_index) inside a chunk's frame section; (size_t)-1 on a bad argument. */
+size_t kvc_frame_size(const kvc_layout* layout);
+size_t kvc_frame_offset(const kvc_layout* layout, int32_t kind, int32_t layer_group, int32_t frame_index);
+
+/* Order in which kvc_fetch_pipeline_frames moves the frames of a request. */
+typedef enum kvc_fetch_order {
+  KVC_ORDER_CHUNK = 0, /* chunk by chunk, each chunk in storage order                  */
+  KVC_ORDER_LAYER = 1  /* layer group by layer group (Appx A.3: the preallocated cache
+                          is filled layer by layer so that inference can start on the
+                          first layers while later ones are still being fetched); inside
+                          a group chunk by chunk, K frames then V frames                 */
+} kvc_fetch_order;
+
+/* Bytes one meta staging buffer of kvc_fetch_pipeline_frames must hold: a whole
+ * chunk meta section (KVC_ORDER_CHUNK) or the pairs of the three layers of one
+ * layer group of one chunk (KVC_ORDER_LAYER).  (size_t)-1 on a bad argument. */
+size_t kvc_meta_staging_size(const kvc_layout* layout, int32_t order);
+
+/* Pipelined fetcher at frame granularity: as kvc_fetch_pipeline, but the device
+ * staging holds a few frames and a few meta pieces instead of whole chunk
+ * blobs -- the frame-wise decompress buffer of Sec. 3.3.2 -- and the order of the
+ * frames is selectable.  Runs of consecutive frames are copied into a frame
+ * staging buffer until it is full (it holds floor(frame_staging_bytes /
+ * kvc_frame_size) frames, at most a chunk's), announced with one event and
+ * restored with one kvc_restore_paged_frames launch per run; the pairs a run
+ * needs are copied before it.
+ *   d_frame_staging  HOST array of n_frame_staging (2..64) DEVICE buffers of
+ *                    frame_staging_bytes >= kvc_frame_size, 256-byte aligned
+ *   d_meta_staging   HOST array of n_meta_staging (2..64) DEVICE buffers of
+ *                    meta_staging_bytes >= kvc_meta_staging_size(layout, order),
+ *                    256-byte aligned
+ *   order            a kvc_fetch_order
+ *   group_ready_events  HOST array of LG hipEvent_t created by the caller, or
+ *                    NULL.  Event g is recorded on compute_stream once every
+ *                    token of layers 3g .. 3g+2 (K and V, all chunks) is in the
+ *                    cache: the per-layer state an engine needs for the
+ *                    non-blocking condition of Appx A.3 (kvc_admission_*).
+ *   group_ready_ms   HOST out float[LG] or NULL: time from the first copy being
+ *                    enqueued to each group being ready.
+ *   fetch_to_ready_ms HOST out or NULL.  The call blocks until the last restore
+ *                    has finished if either time output is non-NULL; otherwise it
+ *                    returns after enqueueing.
+ * Other arguments, blob format and error behaviour as kvc_fetch_pipeline. */
+kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_chunk* chunks, int32_t n_chunks,
+                                     void* const* d_frame_staging, size_t frame_staging_bytes, int32_t n_frame_staging,
+                                     void* const* d_meta_staging, size_t meta_staging_bytes, int32_t n_meta_staging,
+                                     void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
+                                     const int32_t* d_block_table, int64_t table_len, uint32_t* d_err, void* copy_stream,
+                                     void* compute_stream, int32_t order, void* const* group_ready_events,
+                                     float* group_ready_ms, float* fetch_to_ready_ms);
+
+/* Non-blocking condition of the layer-wise fetching-inference pipeline (Appx
+ * A.3), host arithmetic only.  Stage j (1-based in the paper, index j-1 here) is
+ * a layer or a layer group; t_fetch[j-1] is the time to make its KV ready (the
+ * paper's per-layer decoding time), t_comp[j-1] its inference time.  With
+ * n_buffered stages already in the cache the request may join the running
+ * queue iff for every k in n_buffered+1 .. n_stages
+ *     sum_{j=1..k} t_fetch[j] <= sum_{j=1..k-1} t_comp[j].
+ * kvc_admission_ok returns 1 if the condition holds, 0 if not, -1 on a bad
+ * argument (NULL, n_stages < 1, n_buffered outside 0..n_stages, a negative or
+ * non-finite time).  kvc_admission_min_buffered returns the smallest n_buffered
+ * for which it holds (n_stages if every stage must be buffered first), -1 on a
+ * bad argument.  Sums are accumulated in double in index order. */
+int32_t kvc_admission_ok(const double* t_fetch, const double* t_comp, int32_t n_stages, int32_t n_buffered);
+int32_t kvc_admission_min_buffered(const double* t_fetch, const double* t_comp, int32_t n_stages);
 
 /* Static, never-freed description of a status code. */
 const char* kvc_status_str(kvc_status status);

@@ -319,3 +319,42 @@ int kvco_restore_paged(const kvco_layout* lo, const uint8_t* frames, const float
   if (err && bad) *err |= 1u;
   return 0;
 }
+
+/* One decoded frame -> paged slots (Sec. 3.3.2, frame-wise restoration).  The frame is addressed
+ * with the chunk-section formula minus the offset of the frame's first byte. */
+int kvco_restore_paged_frame(const kvco_layout* lo, const uint8_t* frame, const float* meta, int kind, int lg, int f,
+                             int64_t first_token, int64_t n_tokens, uint16_t* const* layer_cache, int64_t num_blocks,
+                             int32_t block_size, const int32_t* block_table, int64_t table_len, uint32_t* err) {
+  if (kvco_check(lo) || first_token < 0 || first_token % lo->T != 0) return 1;
+  if (n_tokens < 1 || n_tokens > lo->T || num_blocks < 1 || block_size < 1) return 1;
+  const int64_t F = kvco_frames_per_group(lo);
+  if (kind < 0 || kind > 1 || lg < 0 || lg >= layer_groups(lo) || f < 0 || f >= F) return 1;
+  if (!frame || !meta || !layer_cache || !block_table) return 1;
+  if (table_len * block_size < first_token + n_tokens) return 1;
+  const int64_t C = (int64_t)lo->H * lo->D;
+  /* first byte of this frame inside the chunk section: plane 0 of layer 3*lg, token f, element 0 sits at
+   * tile position 0 of frame f */
+  const int64_t frame_start = kvco_frame_offset(lo, kind, 3 * lg, f, 0, 0);
+  int bad = 0;
+  for (int pl = 0; pl < 3; ++pl) {
+    const int l = 3 * lg + pl;
+    if (l >= lo->L) continue;
+    for (int64_t t = f; t < n_tokens; t += F) { /* Sec. 3.2.1 step 3: tensor number f of every group */
+      const int64_t p = first_token + t;
+      const int64_t phys = block_table[p / block_size];
+      if (phys < 0 || phys >= num_blocks) {
+        bad = 1;
+        continue;
+      }
+      uint16_t* slot = layer_cache[l] + (((int64_t)kind * num_blocks + phys) * block_size + p % block_size) * C;
+      for (int h = 0; h < lo->H; ++h)
+        for (int d = 0; d < lo->D; ++d) {
+          const uint8_t code = frame[kvco_frame_offset(lo, kind, l, t, h, d) - frame_start];
+          const int64_t mo = kvco_meta_offset(lo, kind, l, t, h, d);
+          slot[(int64_t)h * lo->D + d] = kvco_narrow(kvco_dequantize(code, meta[mo], meta[mo + 1]), lo->dtype);
+        }
+    }
+  }
+  if (err && bad) *err |= 1u;
+  return 0;
+}

@@ -16,14 +16,16 @@
  *   Sec. 3.2.2 rules i-iii       tile = row-major reshape of the H*D vector,
  *                                heads and in-head order kept (tiles (8,512),
  *                                (8,128), (16,64) in the closing paragraph)
- *   Sec. 4 item (1)              "quantized to integers" before encoding; chunking
+ *   Sec. 4 item (1)              tensors become integers before encoding; chunking
  *   Sec. 3.3.2 restoration       frame -> KV tensor -> preallocated paged slots
  *
  * Pins (tests marked "not gpu"): index map against the paper's three worked
  * tiles and rules i-iii, the temporal-alignment and three-plane statements,
  * brute-force bijection, a layout special case equal to a numpy reshape, the
  * uniform-quantizer error bound, exact extremes, numpy's own float16 rounding,
- * paged placement against a poison-filled cache.  Compression ratio, accuracy
+ * paged placement against a poison-filled cache, the frame-wise restore against
+ * the set of tokens and layers a frame carries (Sec. 3.2.1 step 3) and against
+ * the chunk-level restore.  Compression ratio, accuracy
  * and TTFT of the paper need a codec, weights and datasets: parity unpinned,
  * and not computed here.
  */
@@ -72,5 +74,12 @@ int kvco_restore(const kvco_layout* lo, const uint8_t* frames, const float* meta
 int kvco_restore_paged(const kvco_layout* lo, const uint8_t* frames, const float* meta, int64_t first_token,
                        int64_t n_tokens, uint16_t* const* layer_cache, int64_t num_blocks, int32_t block_size,
                        const int32_t* block_table, int64_t table_len, uint32_t* err);
+/* Frame-wise restoration (Sec. 3.3.2): `frame` holds the three planes of (kind, layer group lg,
+ * frame index f) of the chunk that starts at sequence position first_token and has n_tokens
+ * valid tokens; meta is that chunk's meta section.  Writes the tokens t with t % F == f of the
+ * layers 3*lg .. 3*lg+2 that exist. */
+int kvco_restore_paged_frame(const kvco_layout* lo, const uint8_t* frame, const float* meta, int kind, int lg, int f,
+                             int64_t first_token, int64_t n_tokens, uint16_t* const* layer_cache, int64_t num_blocks,
+                             int32_t block_size, const int32_t* block_table, int64_t table_len, uint32_t* err);
 int kvco_threads(void); /* threads the chunk/layer loops run on */
 #endif

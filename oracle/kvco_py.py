@@ -48,6 +48,7 @@ def lib():
         _lib.kvco_pack.argtypes = [LP, p, i64, i64, i64, i64, p, p]
         _lib.kvco_restore.argtypes = [LP, p, p, i64, p, i64, i64, i64]
         _lib.kvco_restore_paged.argtypes = [LP, p, p, i64, i64, p, i64, C.c_int32, p, i64, p]
+        _lib.kvco_restore_paged_frame.argtypes = [LP, p, p, C.c_int, C.c_int, C.c_int, i64, i64, p, i64, C.c_int32, p, i64, p]
         _lib.kvco_threads.restype = C.c_int
     return _lib
 
@@ -155,4 +156,27 @@ def restore_paged(lo, frames, meta, first_token, n_tokens, caches, num_blocks, b
                                   num_blocks, block_size, bt.ctypes.data, bt.size, C.byref(err))
     if rc:
         raise ValueError("kvco_restore_paged rejected its arguments")
+    return err.value
+
+
+def frame_size(lo):
+    """bytes of one frame: three planes"""
+    return 3 * lo.TY * lo.th * lo.TX * lo.tw
+
+
+def frame_start(lo, kind, lg, f):
+    """offset of frame (kind, lg, f) inside a chunk's frame section"""
+    return frame_offset(lo, kind, 3 * lg, f, 0, 0)
+
+
+def restore_paged_frame(lo, frame, meta, kind, lg, f, first_token, n_tokens, caches, num_blocks, block_size, block_table):
+    assert frame.dtype == np.uint8 and frame.size == frame_size(lo) and meta.dtype == np.float32
+    ptrs = (C.c_void_p * lo.L)(*[c.ctypes.data for c in caches])
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    err = C.c_uint32(0)
+    frame = np.ascontiguousarray(frame)
+    rc = lib().kvco_restore_paged_frame(C.byref(lo), frame.ctypes.data, meta.ctypes.data, kind, lg, f, first_token,
+                                        n_tokens, ptrs, num_blocks, block_size, bt.ctypes.data, bt.size, C.byref(err))
+    if rc:
+        raise ValueError("kvco_restore_paged_frame rejected its arguments")
     return err.value

@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 
 #include <limits.h>
+#include <string.h>
+
+#include <vector>
 
 #include "kvc_launch.h"
 
@@ -210,6 +213,354 @@ kvc_status kvc_restore_paged(const kvc_layout* layout, const uint8_t* frames, co
   p.frames = frames;
   p.meta = static_cast<const float*>(meta);
   return launch_restore(p, true, as_stream(stream));
+}
+
+size_t kvc_frame_size(const kvc_layout* layout) {
+  Geo g;
+  if (make_geo(layout, &g) != KVC_OK) return (size_t)-1;
+  return (size_t)(3 * g.plane);
+}
+
+size_t kvc_frame_offset(const kvc_layout* layout, int32_t kind, int32_t layer_group, int32_t frame_index) {
+  Geo g;
+  if (make_geo(layout, &g) != KVC_OK) return (size_t)-1;
+  if (kind < 0 || kind > 1 || layer_group < 0 || layer_group >= g.LG || frame_index < 0 || frame_index >= g.F)
+    return (size_t)-1;
+  return (size_t)((((int64_t)kind * g.LG + layer_group) * g.F + frame_index) * 3 * g.plane);
+}
+
+namespace {
+
+// Fills the frame-call fields after fill_paged; first_token / n_tokens describe the chunk.
+kvc_status fill_frames_args(RestoreParams& p, const uint8_t* frames, const void* meta, int64_t first_frame, int64_t n_frames,
+                       int64_t n_tokens) {
+  const int64_t per_chunk = (int64_t)2 * p.g.LG * p.g.F;
+  if (first_frame < 0 || n_frames < 1 || first_frame >= per_chunk || n_frames > per_chunk - first_frame)
+    return KVC_ERR_INVALID_ARG;
+  if (n_tokens < 1 || n_tokens > p.g.T) return KVC_ERR_INVALID_ARG;
+  if (!frames || !meta || !aligned(frames, 8) || !aligned(meta, 8)) return KVC_ERR_INVALID_ARG;  // 8-byte code loads
+  p.frames = frames;
+  p.meta = static_cast<const float*>(meta);
+  p.frame_mode = 1;
+  p.fm_first = (int32_t)first_frame;
+  p.fm_count = (int32_t)n_frames;
+  return KVC_OK;
+}
+
+}  // namespace
+
+kvc_status kvc_restore_paged_frames(const kvc_layout* layout, const uint8_t* frames, const void* meta, int64_t first_frame,
+                                    int64_t n_frames, int64_t first_token, int64_t n_tokens, void* const* d_layer_cache,
+                                    int64_t num_blocks, int32_t block_size, const int32_t* d_block_table,
+                                    int64_t table_len, uint32_t* d_err, void* stream) {
+  RestoreParams p{};
+  kvc_status st = make_geo(layout, &p.g);
+  if (st != KVC_OK) return st;
+  if ((st = fill_paged(p, first_token, n_tokens, d_layer_cache, num_blocks, block_size, d_block_table, table_len,
+                       d_err)) != KVC_OK)
+    return st;
+  if ((st = fill_frames_args(p, frames, meta, first_frame, n_frames, n_tokens)) != KVC_OK) return st;
+  return launch_restore(p, true, as_stream(stream));
+}
+
+kvc_status kvc_restore_paged_frame(const kvc_layout* layout, const uint8_t* frame, const void* meta, int32_t kind,
+                                   int32_t layer_group, int32_t frame_index, int64_t first_token, int64_t n_tokens,
+                                   void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
+                                   const int32_t* d_block_table, int64_t table_len, uint32_t* d_err, void* stream) {
+  Geo g;
+  kvc_status st = make_geo(layout, &g);
+  if (st != KVC_OK) return st;
+  if (kind < 0 || kind > 1 || layer_group < 0 || layer_group >= g.LG || frame_index < 0 || frame_index >= g.F)
+    return KVC_ERR_INVALID_ARG;
+  return kvc_restore_paged_frames(layout, frame, meta, ((int64_t)kind * g.LG + layer_group) * g.F + frame_index, 1,
+                                  first_token, n_tokens, d_layer_cache, num_blocks, block_size, d_block_table, table_len,
+                                  d_err, stream);
+}
+
+namespace {
+
+// {scale, mn} pairs of one layer of one chunk for a kind.
+int64_t pairs_per_layer(const Geo& g, int kind) {
+  return g.mode[kind] == KVC_Q_PER_CHANNEL ? (int64_t)g.C : (int64_t)g.T * g.H;
+}
+
+// Events of one staging ring: "copied" after the H2D copy into a slot, "freed"
+// after the last kernel that read it.
+struct Ring {
+  hipEvent_t copied[64], freed[64];
+  int n = 0;
+  bool create(int slots) {
+    for (; n < slots; ++n) {
+      if (hipEventCreateWithFlags(&copied[n], hipEventDisableTiming) != hipSuccess) return false;
+      if (hipEventCreateWithFlags(&freed[n], hipEventDisableTiming) != hipSuccess) {
+        (void)hipEventDestroy(copied[n]);
+        return false;
+      }
+    }
+    return true;
+  }
+  void destroy() {
+    for (int i = 0; i < n; ++i) {
+      (void)hipEventDestroy(copied[i]);
+      (void)hipEventDestroy(freed[i]);
+    }
+    n = 0;
+  }
+};
+
+}  // namespace
+
+size_t kvc_meta_staging_size(const kvc_layout* layout, int32_t order) {
+  Geo g;
+  if (make_geo(layout, &g) != KVC_OK) return (size_t)-1;
+  if (order == KVC_ORDER_CHUNK) return (size_t)g.meta_floats * 4;
+  if (order != KVC_ORDER_LAYER) return (size_t)-1;
+  return (size_t)(3 * (pairs_per_layer(g, 0) + pairs_per_layer(g, 1)) * 8);
+}
+
+kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_chunk* chunks, int32_t n_chunks,
+                                     void* const* d_frame_staging, size_t frame_staging_bytes, int32_t n_frame_staging,
+                                     void* const* d_meta_staging, size_t meta_staging_bytes, int32_t n_meta_staging,
+                                     void* const* d_layer_cache, int64_t num_blocks, int32_t block_size,
+                                     const int32_t* d_block_table, int64_t table_len, uint32_t* d_err, void* copy_stream,
+                                     void* compute_stream, int32_t order, void* const* group_ready_events,
+                                     float* group_ready_ms, float* fetch_to_ready_ms) {
+  RestoreParams base{};
+  kvc_status st = make_geo(layout, &base.g);
+  if (st != KVC_OK) return st;
+  const Geo& g = base.g;
+  if (order != KVC_ORDER_CHUNK && order != KVC_ORDER_LAYER) return KVC_ERR_INVALID_ARG;
+  if (n_chunks < 0 || n_chunks > 4096) return KVC_ERR_INVALID_ARG;
+  if (n_chunks == 0) {
+    if (fetch_to_ready_ms) *fetch_to_ready_ms = 0.f;
+    if (group_ready_ms)
+      for (int lg = 0; lg < g.LG; ++lg) group_ready_ms[lg] = 0.f;
+    return KVC_OK;
+  }
+  if (!chunks || !d_frame_staging || !d_meta_staging) return KVC_ERR_INVALID_ARG;
+  if (n_frame_staging < 2 || n_frame_staging > 64 || n_meta_staging < 2 || n_meta_staging > 64) return KVC_ERR_INVALID_ARG;
+  if (!copy_stream || !compute_stream || copy_stream == compute_stream) return KVC_ERR_INVALID_ARG;
+  const size_t meta_off = kvc_blob_meta_offset(layout);
+  const size_t meta_bytes = (size_t)g.meta_floats * 4, frame_size = (size_t)(3 * g.plane);
+  const size_t blob_bytes = meta_off + meta_bytes;
+  if (frame_staging_bytes < frame_size || meta_staging_bytes < kvc_meta_staging_size(layout, order))
+    return KVC_ERR_BUFFER_TOO_SMALL;
+  int64_t total = 0;
+  for (int i = 0; i < n_chunks; ++i) {
+    if (!chunks[i].host_blob) return KVC_ERR_INVALID_ARG;
+    if (chunks[i].bytes < blob_bytes) return KVC_ERR_BUFFER_TOO_SMALL;
+    if (chunks[i].n_tokens < 1 || chunks[i].n_tokens > g.T) return KVC_ERR_INVALID_ARG;
+    if (i + 1 < n_chunks && chunks[i].n_tokens != g.T) return KVC_ERR_INVALID_ARG;
+    total += chunks[i].n_tokens;
+  }
+  for (int s = 0; s < n_frame_staging; ++s)
+    if (!d_frame_staging[s] || !aligned(d_frame_staging[s], 256)) return KVC_ERR_INVALID_ARG;
+  for (int s = 0; s < n_meta_staging; ++s)
+    if (!d_meta_staging[s] || !aligned(d_meta_staging[s], 256)) return KVC_ERR_INVALID_ARG;
+  if (group_ready_events)
+    for (int lg = 0; lg < g.LG; ++lg)
+      if (!group_ready_events[lg]) return KVC_ERR_INVALID_ARG;
+  if ((st = fill_paged(base, 0, total, d_layer_cache, num_blocks, block_size, d_block_table, table_len, d_err)) != KVC_OK)
+    return st;
+
+  hipStream_t cs = as_stream(copy_stream), xs = as_stream(compute_stream);
+  const bool blocking = fetch_to_ready_ms || group_ready_ms;
+  Ring frames_ring, meta_ring;
+  hipEvent_t t_begin = nullptr, t_end = nullptr;
+  std::vector<hipEvent_t> t_group;  // timing events of the layer groups
+  bool ok = frames_ring.create(n_frame_staging) && meta_ring.create(n_meta_staging);
+  if (ok && blocking) ok = hipEventCreate(&t_begin) == hipSuccess && hipEventCreate(&t_end) == hipSuccess;
+  if (ok && group_ready_ms)
+    for (int lg = 0; lg < g.LG && ok; ++lg) {
+      hipEvent_t e = nullptr;
+      ok = hipEventCreate(&e) == hipSuccess;
+      if (ok) t_group.push_back(e);
+    }
+  kvc_status result = ok ? KVC_OK : KVC_ERR_RUNTIME;
+
+  // A slot of the frame ring is filled with pieces: runs of consecutive frames of one chunk,
+  // copied back to back and announced with one event.  A piece reads the pairs of its meta
+  // unit: the whole meta section of its chunk (chunk order) or the pairs of one layer group
+  // of one chunk (layer order).
+  struct Piece {
+    int chunk;
+    int64_t first, count;  // frames of the chunk
+    size_t slot_off;       // bytes from the slot start
+    int meta_slot;
+    int lg;                // layer order: the group whose pairs the meta slot holds
+    bool ends_unit;        // last piece that reads the meta slot's present content
+  };
+  const int64_t per_chunk = (int64_t)2 * g.LG * g.F;
+  int64_t per_slot = (int64_t)(frame_staging_bytes / frame_size);
+  if (per_slot > per_chunk) per_slot = per_chunk;
+  std::vector<Piece> fill;       // pieces of the slot being filled
+  int64_t fill_frames = 0;       // frames already in it
+  int64_t fill_no = 0;           // slots filled so far
+  int64_t fill_first_unit = 0;   // running number of the meta unit of the fill's first piece
+  int64_t unit_no = -1;          // running number of the current meta unit
+
+  auto flush = [&]() {
+    if (fill.empty() || !ok) return;
+    const int fs = (int)(fill_no % n_frame_staging);
+    ok = hipEventRecord(frames_ring.copied[fs], cs) == hipSuccess;  // covers the meta copies before it, too
+    if (ok) ok = hipStreamWaitEvent(xs, frames_ring.copied[fs], 0) == hipSuccess;
+    for (size_t k = 0; k < fill.size() && ok; ++k) {
+      const Piece& pc = fill[k];
+      RestoreParams p = base;
+      p.first_token = (int64_t)pc.chunk * g.T;
+      p.n_tokens = chunks[pc.chunk].n_tokens;
+      kvc_status ls = fill_frames_args(p, static_cast<const uint8_t*>(d_frame_staging[fs]) + pc.slot_off,
+                                       d_meta_staging[pc.meta_slot], pc.first, pc.count, chunks[pc.chunk].n_tokens);
+      if (order == KVC_ORDER_LAYER) {
+        p.meta_sliced = 1;
+        p.meta_l0 = 3 * pc.lg;
+        p.moff[0] = 0;
+        p.moff[1] = 3 * pairs_per_layer(g, 0) * 2;
+      }
+      if (ls == KVC_OK) ls = launch_restore(p, true, xs);
+      if (ls != KVC_OK) {
+        result = ls;
+        ok = false;
+        break;
+      }
+      if (pc.ends_unit) ok = hipEventRecord(meta_ring.freed[pc.meta_slot], xs) == hipSuccess;
+      // Layer group lg is complete once the last V frame of the last chunk has been restored
+      // (everything else of the group is earlier in both orders).
+      if (pc.chunk == n_chunks - 1)
+        for (int lg = 0; lg < g.LG && ok; ++lg) {
+          const int64_t last = ((int64_t)g.LG + lg) * g.F + g.F - 1;
+          if (last < pc.first || last >= pc.first + pc.count) continue;
+          if (group_ready_events) ok = hipEventRecord(static_cast<hipEvent_t>(group_ready_events[lg]), xs) == hipSuccess;
+          if (ok && group_ready_ms) ok = hipEventRecord(t_group[lg], xs) == hipSuccess;
+        }
+    }
+    if (ok) ok = hipEventRecord(frames_ring.freed[fs], xs) == hipSuccess;
+    fill.clear();
+    fill_frames = 0;
+    ++fill_no;
+  };
+
+  // Starts the meta unit of (chunk i, layer group lg or -1 for the whole section) and returns its slot.
+  auto begin_unit = [&](int i, int lg) -> int {
+    ++unit_no;
+    // the slot about to be overwritten may still be needed by a piece of the unfinished fill
+    if (!fill.empty() && fill_first_unit + n_meta_staging <= unit_no) flush();
+    const int ms = (int)(unit_no % n_meta_staging);
+    const uint8_t* src = static_cast<const uint8_t*>(chunks[i].host_blob) + meta_off;
+    uint8_t* dst = static_cast<uint8_t*>(d_meta_staging[ms]);
+    if (ok && unit_no >= n_meta_staging) ok = hipStreamWaitEvent(cs, meta_ring.freed[ms], 0) == hipSuccess;
+    if (lg < 0) {
+      if (ok) ok = hipMemcpyAsync(dst, src, meta_bytes, hipMemcpyHostToDevice, cs) == hipSuccess;
+    } else {
+      const int nl = g.L - 3 * lg < 3 ? g.L - 3 * lg : 3;
+      for (int kind = 0; kind < 2 && ok; ++kind) {
+        const int64_t ppl = pairs_per_layer(g, kind);
+        ok = hipMemcpyAsync(dst + (kind ? 3 * pairs_per_layer(g, 0) * 8 : 0),
+                            src + (g.meta_off[kind] + 3 * lg * ppl * 2) * 4, (size_t)(nl * ppl * 8),
+                            hipMemcpyHostToDevice, cs) == hipSuccess;
+      }
+    }
+    return ms;
+  };
+
+  // Appends frames [first, first + count) of chunk i, cut into pieces that fit a slot.
+  auto add_run = [&](int i, int64_t first, int64_t count, int ms, int lg, bool last_of_unit) {
+    const uint8_t* blob = static_cast<const uint8_t*>(chunks[i].host_blob);
+    while (count > 0 && ok) {
+      if (fill_frames == per_slot) flush();
+      const int64_t n = count < per_slot - fill_frames ? count : per_slot - fill_frames;
+      const int fs = (int)(fill_no % n_frame_staging);
+      if (fill.empty()) {
+        fill_first_unit = unit_no;
+        if (fill_no >= n_frame_staging) ok = hipStreamWaitEvent(cs, frames_ring.freed[fs], 0) == hipSuccess;
+      }
+      const size_t off = (size_t)fill_frames * frame_size;
+      if (ok)
+        ok = hipMemcpyAsync(static_cast<uint8_t*>(d_frame_staging[fs]) + off, blob + (size_t)first * frame_size,
+                            (size_t)n * frame_size, hipMemcpyHostToDevice, cs) == hipSuccess;
+      fill.push_back(Piece{i, first, n, off, ms, lg, last_of_unit && n == count});
+      fill_frames += n;
+      first += n;
+      count -= n;
+    }
+  };
+
+  if (ok) {
+    if (t_begin) ok = hipEventRecord(t_begin, cs) == hipSuccess;
+    if (order == KVC_ORDER_CHUNK) {
+      for (int i = 0; i < n_chunks && ok; ++i) {
+        const int ms = begin_unit(i, -1);
+        add_run(i, 0, per_chunk, ms, -1, true);
+      }
+    } else {
+      // Appx A.3: the cache is filled layer by layer, so group 0 of every chunk comes first.
+      for (int lg = 0; lg < g.LG && ok; ++lg)
+        for (int i = 0; i < n_chunks && ok; ++i) {
+          const int ms = begin_unit(i, lg);
+          add_run(i, (int64_t)lg * g.F, g.F, ms, lg, false);                   // K frames of the group
+          add_run(i, ((int64_t)g.LG + lg) * g.F, g.F, ms, lg, true);           // V frames of the group
+        }
+    }
+    flush();
+    if (!ok && result == KVC_OK) result = KVC_ERR_RUNTIME;
+    if (blocking) {
+      if (hipEventRecord(t_end, xs) != hipSuccess || hipEventSynchronize(t_end) != hipSuccess) {
+        if (result == KVC_OK) result = KVC_ERR_RUNTIME;
+      } else if (result == KVC_OK) {
+        if (fetch_to_ready_ms && hipEventElapsedTime(fetch_to_ready_ms, t_begin, t_end) != hipSuccess)
+          result = KVC_ERR_RUNTIME;
+        if (group_ready_ms)
+          for (int lg = 0; lg < g.LG && result == KVC_OK; ++lg)
+            if (hipEventElapsedTime(&group_ready_ms[lg], t_begin, t_group[lg]) != hipSuccess) result = KVC_ERR_RUNTIME;
+      }
+    }
+    if (result != KVC_OK) {
+      (void)hipStreamSynchronize(cs);
+      (void)hipStreamSynchronize(xs);
+    }
+  }
+  frames_ring.destroy();
+  meta_ring.destroy();
+  for (hipEvent_t e : t_group) (void)hipEventDestroy(e);
+  if (t_begin) (void)hipEventDestroy(t_begin);
+  if (t_end) (void)hipEventDestroy(t_end);
+  return result;
+}
+
+namespace {
+
+// Finite and not negative.  Tested on the bit pattern: this library is compiled with the
+// assumption that no NaN occurs, so a floating-point comparison cannot be trusted to see one.
+bool good_times(const double* t, int32_t n) {
+  for (int32_t i = 0; i < n; ++i) {
+    uint64_t b;
+    memcpy(&b, &t[i], sizeof b);
+    const bool negative = (b >> 63) != 0 && (b << 1) != 0;  // -0.0 counts as zero
+    if (negative || ((b >> 52) & 0x7ffu) == 0x7ffu) return false;
+  }
+  return true;
+}
+
+}  // namespace
+
+int32_t kvc_admission_min_buffered(const double* t_fetch, const double* t_comp, int32_t n_stages) {
+  if (!t_fetch || !t_comp || n_stages < 1 || !good_times(t_fetch, n_stages) || !good_times(t_comp, n_stages)) return -1;
+  // The condition for k does not depend on n_buffered, so the answer is the largest k that violates it.
+  double fetched = 0.0, computed = 0.0;  // sum_{j<=k} t_fetch, sum_{j<=k-1} t_comp
+  int32_t need = 0;
+  for (int32_t k = 1; k <= n_stages; ++k) {
+    fetched += t_fetch[k - 1];
+    if (k >= 2) computed += t_comp[k - 2];
+    if (fetched > computed) need = k;
+  }
+  return need;
+}
+
+int32_t kvc_admission_ok(const double* t_fetch, const double* t_comp, int32_t n_stages, int32_t n_buffered) {
+  if (n_buffered < 0 || n_buffered > n_stages) return -1;
+  const int32_t need = kvc_admission_min_buffered(t_fetch, t_comp, n_stages);
+  if (need < 0) return -1;
+  return n_buffered >= need ? 1 : 0;
 }
 
 kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* chunks, int32_t n_chunks,

@@ -21,7 +21,16 @@ struct RestoreParams {
   FastDiv dtbc, dL;       // unit -> (token block, layer, kind, chunk)
   FastDiv dapt;           // atoms per token
   FastDiv dwpt;           // waves per token (apt / 64) when apt is a multiple of 64
-  uint32_t frame_stride;     // bytes from a frame to the next of the same layer group: 3 planes
+  uint32_t frame_stride;     // bytes from a frame to the next of the same layer group: 3 planes (0 for a frame call)
+  // frame call: `frames` holds fm_count consecutive frames (three planes each), the first being
+  // frame number fm_first = (kind * LG + layer group) * F + frame index of its chunk
+  int32_t frame_mode, fm_first, fm_count;
+  FastDiv dLG;
+  // Where the pairs of (kind, layer l) start: meta + chunk * meta_floats + moff[kind] + (l - meta_l0) * pairs per
+  // layer * 2 floats.  A whole chunk section has meta_l0 = 0 and the section's own offsets (set by launch_restore
+  // unless meta_sliced); a frame call may bring only the layers of its layer group.
+  int32_t meta_sliced, meta_l0;
+  int64_t moff[2];
   uint32_t tile_row_stride;  // bytes from a row of tiles to the next: th * W
   // contiguous destination
   uint16_t* out;

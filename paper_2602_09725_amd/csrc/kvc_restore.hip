@@ -89,7 +89,7 @@ __device__ __forceinline__ void load_channel_pairs(const float* mbase, int64_t f
 
 template <int MODE, int DT, bool PAGED>
 __device__ __forceinline__ void restore_body_waves(const RestoreParams& p, uint32_t c, uint32_t kind, uint32_t l,
-                                                   uint32_t tbi) {
+                                                   uint32_t tbi, const uint8_t* fsec, uint32_t ff) {
   constexpr int U = KVC_RESTORE_U;
   const Geo& g = p.g;
   const uint32_t lane = threadIdx.x & 63u;
@@ -101,13 +101,17 @@ __device__ __forceinline__ void restore_body_waves(const RestoreParams& p, uint3
   const int64_t chunk_first = (int64_t)c * g.T;
   const int64_t left = p.n_tokens - chunk_first;
   const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;  // valid tokens of this chunk
-  // Tokens of this workgroup: tb consecutive tokens; pass k of this wave takes token t0 + tsub + k * tpp.
+  // Token slots of this workgroup: tb consecutive slots; pass k of this wave takes slot
+  // t0 + tsub + k * tpp.  Slot s is token s (chunk call) or token s * F + f (frame call:
+  // only the tokens whose tile sits in frame f of their group, Sec. 3.2.1 step 3).
+  const int32_t ns = p.frame_mode ? (n > (int32_t)ff ? (n - (int32_t)ff + g.F - 1) / g.F : 0) : n;
   const int32_t t0 = (int32_t)tbi * p.tb;
-  const int32_t t1 = t0 + p.tb < n ? t0 + p.tb : n;
+  const int32_t t1 = t0 + p.tb < ns ? t0 + p.tb : ns;
   if (t0 >= t1) return;
   const int32_t t = t0 + (int32_t)tsub + (int32_t)lane * p.tpp;
   const bool in_range = t < t1;
-  const uint32_t tc = (uint32_t)(in_range ? t : t0);  // clamp: loads of dead passes stay in bounds
+  const uint32_t tslot = (uint32_t)(in_range ? t : t0);  // clamp: loads of dead passes stay in bounds
+  const uint32_t tc = p.frame_mode ? tslot * (uint32_t)g.F + ff : tslot;
   // inter-frame layout: token -> (frame of its group, tile position of its group)
   uint32_t gi, f, ty, tx;
   fd_divmod(g.dF, tc, gi, f);
@@ -134,16 +138,15 @@ __device__ __forceinline__ void restore_body_waves(const RestoreParams& p, uint3
   // ---- per-lane constants
   uint32_t r, cc;
   fd_divmod(g.dtw, e, r, cc);  // intra-frame layout: element -> (row, column) of the tile
-  const uint32_t lg = l / 3u, pl = l - lg * 3u;
-  const uint8_t* fsec = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane;
   const uint32_t src_lane = r * (uint32_t)g.W + cc;
-  const float* mbase = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind];
+  const float* mbase = p.meta + (int64_t)c * g.meta_floats + p.moff[kind];
+  const uint32_t lm = l - (uint32_t)p.meta_l0;  // layer index inside the pairs that `meta` holds
   float sc[8], mn[8];
   const uint8_t* mrow = nullptr;
   if (MODE == KVC_Q_PER_CHANNEL) {
-    load_channel_pairs(mbase, (int64_t)l * g.C + e, sc, mn);
+    load_channel_pairs(mbase, (int64_t)lm * g.C + e, sc, mn);
   } else {
-    mrow = reinterpret_cast<const uint8_t*>(mbase + 2 * ((int64_t)l * g.T * g.H + fd_div(g.dD, e)));
+    mrow = reinterpret_cast<const uint8_t*>(mbase + 2 * ((int64_t)lm * g.T * g.H + fd_div(g.dD, e)));
   }
   uint8_t* obase;
   if (PAGED)
@@ -176,7 +179,7 @@ __device__ __forceinline__ void restore_body_waves(const RestoreParams& p, uint3
 
 template <int MODE, int DT, bool PAGED>
 __device__ __forceinline__ void restore_body_lanes(const RestoreParams& p, uint32_t c, uint32_t kind, uint32_t l,
-                                                   uint32_t tbi) {
+                                                   uint32_t tbi, const uint8_t* fsec, uint32_t ff) {
   constexpr int U = KVC_RESTORE_U;
   const Geo& g = p.g;
   const uint32_t tid = threadIdx.x;
@@ -186,22 +189,22 @@ __device__ __forceinline__ void restore_body_lanes(const RestoreParams& p, uint3
   const int64_t chunk_first = (int64_t)c * g.T;
   const int64_t left = p.n_tokens - chunk_first;
   const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
+  const int32_t ns = p.frame_mode ? (n > (int32_t)ff ? (n - (int32_t)ff + g.F - 1) / g.F : 0) : n;  // token slots, as above
   const int32_t t0 = (int32_t)tbi * p.tb;
-  const int32_t t1 = t0 + p.tb < n ? t0 + p.tb : n;
+  const int32_t t1 = t0 + p.tb < ns ? t0 + p.tb : ns;
   if (t0 >= t1) return;
 
   uint32_t r, cc;
   fd_divmod(g.dtw, e, r, cc);
-  const uint32_t lg = l / 3u, pl = l - lg * 3u;
-  const uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes +
-                         (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane + (r * (uint32_t)g.W + cc);
-  const float* mbase = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind];
+  const uint8_t* fbase = fsec + (r * (uint32_t)g.W + cc);
+  const float* mbase = p.meta + (int64_t)c * g.meta_floats + p.moff[kind];
+  const uint32_t lm = l - (uint32_t)p.meta_l0;  // layer index inside the pairs that `meta` holds
   float sc[8], mn[8];
   const float* mrow = nullptr;
   if (MODE == KVC_Q_PER_CHANNEL)
-    load_channel_pairs(mbase, (int64_t)l * g.C + e, sc, mn);
+    load_channel_pairs(mbase, (int64_t)lm * g.C + e, sc, mn);
   else
-    mrow = mbase + 2 * ((int64_t)l * g.T * g.H + fd_div(g.dD, e));
+    mrow = mbase + 2 * ((int64_t)lm * g.T * g.H + fd_div(g.dD, e));
   uint16_t* obase;
   if (PAGED)
     obase = reinterpret_cast<uint16_t*>(as_const(p.layer_cache)[l]) + (int64_t)kind * p.num_blocks * p.dbs.d * g.C + e;
@@ -220,7 +223,8 @@ __device__ __forceinline__ void restore_body_lanes(const RestoreParams& p, uint3
     for (int u = 0; u < U; ++u) {
       const int32_t t = tb0 + u * step + (int32_t)tsub;
       live[u] = t < t1;
-      const uint32_t tc = (uint32_t)(live[u] ? t : t1 - 1);
+      const uint32_t tslot = (uint32_t)(live[u] ? t : t1 - 1);
+      const uint32_t tc = p.frame_mode ? tslot * (uint32_t)g.F + ff : tslot;
       uint32_t gi, f, ty, tx;
       fd_divmod(g.dF, tc, gi, f);
       fd_divmod(g.dTX, gi, ty, tx);
@@ -257,20 +261,38 @@ __global__ void __launch_bounds__(1024) restore_kernel(const RestoreParams p) {
   const uint32_t unit = (blockIdx.x & 7u) * p.units_per_xcd + (blockIdx.x >> 3);
 #endif
   if (unit >= p.n_units) return;
-  uint32_t rest, tbi, l;
+  uint32_t rest, tbi, l, kind, c, ff = 0;
+  const uint8_t* fsec;  // plane of layer l: frame 0 of its group (chunk call) or the one frame (frame call)
   fd_divmod(p.dtbc, unit, rest, tbi);
-  fd_divmod(p.dL, rest, rest, l);
-  const uint32_t kind = rest & 1u, c = rest >> 1;
+  if (p.frame_mode) {
+    // `frames` holds fm_count consecutive frames, the first being number fm_first of its chunk in
+    // the order [kind][layer group][frame of the group]; a frame carries the (up to) three layers
+    // of its group, one per plane.
+    const uint32_t frel = rest / 3u, pl = rest - frel * 3u;
+    uint32_t q, lg;
+    fd_divmod(p.g.dF, (uint32_t)p.fm_first + frel, q, ff);
+    fd_divmod(p.dLG, q, kind, lg);
+    l = lg * 3u + pl;
+    c = 0;
+    if (l >= (uint32_t)p.g.L) return;
+    fsec = p.frames + ((int64_t)frel * 3 + pl) * p.g.plane;
+  } else {
+    fd_divmod(p.dL, rest, rest, l);
+    kind = rest & 1u;
+    c = rest >> 1;
+    const uint32_t lg = l / 3u, pl = l - lg * 3u;
+    fsec = p.frames + (int64_t)c * p.g.frame_bytes + (((int64_t)kind * p.g.LG + lg) * p.g.F * 3 + pl) * p.g.plane;
+  }
   if (p.g.mode[kind] == KVC_Q_PER_CHANNEL) {
     if (WAVES)
-      restore_body_waves<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi);
+      restore_body_waves<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
     else
-      restore_body_lanes<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi);
+      restore_body_lanes<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
   } else {
     if (WAVES)
-      restore_body_waves<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi);
+      restore_body_waves<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
     else
-      restore_body_lanes<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi);
+      restore_body_lanes<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
   }
 }
 
@@ -299,19 +321,26 @@ kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream) {
   p.dapt = make_fastdiv((uint32_t)g.apt);
   p.dwpt = make_fastdiv((uint32_t)(waves ? g.apt / 64 : 1));
   if (g.frame_bytes >= (1ll << 32)) return KVC_ERR_UNSUPPORTED;  // offsets inside a chunk section are 32-bit
-  p.frame_stride = (uint32_t)(3 * g.plane);
+  p.frame_stride = p.frame_mode ? 0u : (uint32_t)(3 * g.plane);
+  if (!p.meta_sliced) {  // `meta` holds whole chunk sections
+    p.meta_l0 = 0;
+    p.moff[0] = g.meta_off[0];
+    p.moff[1] = g.meta_off[1];
+  }
   p.tile_row_stride = (uint32_t)g.th * (uint32_t)g.W;
   if (p.tb <= 0) p.tb = waves ? KVC_RESTORE_TB : KVC_RESTORE_TB_LANES;
   if (waves && p.tb > 64 * tpp) p.tb = 64 * tpp;  // one lane per token of a wave
   if (p.tb > g.T) p.tb = g.T;
   p.tbc = (g.T + p.tb - 1) / p.tb;
   p.n_chunks = (int32_t)((p.n_tokens + g.T - 1) / g.T);
-  const int64_t units = (int64_t)p.n_chunks * 2 * g.L * p.tbc;
+  if (p.frame_mode) p.tbc = ((g.T + g.F - 1) / g.F + p.tb - 1) / p.tb;  // slots of one frame
+  const int64_t units = p.frame_mode ? (int64_t)p.fm_count * 3 * p.tbc : (int64_t)p.n_chunks * 2 * g.L * p.tbc;
   if (units > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
   p.n_units = (uint32_t)units;
   p.units_per_xcd = (p.n_units + 7u) / 8u;
   p.dtbc = make_fastdiv((uint32_t)p.tbc);
   p.dL = make_fastdiv((uint32_t)g.L);
+  p.dLG = make_fastdiv((uint32_t)g.LG);
   const dim3 grid(p.units_per_xcd * 8u), block((unsigned)threads);
   if (g.dtype == KVC_F16) {
     if (paged)

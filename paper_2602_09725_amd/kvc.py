@@ -8,6 +8,7 @@ import os
 
 KVC_F16, KVC_BF16 = 0, 1
 KVC_Q_PER_CHANNEL, KVC_Q_PER_TOKEN = 0, 1
+KVC_ORDER_CHUNK, KVC_ORDER_LAYER = 0, 1
 KVC_ABI_VERSION = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -69,6 +70,22 @@ def load(path=None):
     lib.kvc_restore_paged.argtypes = [LP, vp, vp, i64, i64, vp, i64, i32, vp, i64, vp, vp]
     lib.kvc_fetch_pipeline.argtypes = [LP, C.POINTER(HostChunk), i32, C.POINTER(vp), sz, i32, vp, i64, i32, vp, i64,
                                        vp, vp, vp, C.POINTER(C.c_float)]
+    lib.kvc_restore_paged_frame.argtypes = [LP, vp, vp, i32, i32, i32, i64, i64, vp, i64, i32, vp, i64, vp, vp]
+    lib.kvc_restore_paged_frames.argtypes = [LP, vp, vp, i64, i64, i64, i64, vp, i64, i32, vp, i64, vp, vp]
+    lib.kvc_frame_size.argtypes = [LP]
+    lib.kvc_frame_size.restype = sz
+    lib.kvc_frame_offset.argtypes = [LP, i32, i32, i32]
+    lib.kvc_frame_offset.restype = sz
+    lib.kvc_fetch_pipeline_frames.argtypes = [LP, C.POINTER(HostChunk), i32, C.POINTER(vp), sz, i32, C.POINTER(vp), sz, i32,
+                                              vp, i64, i32, vp, i64, vp, vp, vp, i32, C.POINTER(vp),
+                                              C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.kvc_meta_staging_size.argtypes = [LP, i32]
+    lib.kvc_meta_staging_size.restype = sz
+    dp = C.POINTER(C.c_double)
+    lib.kvc_admission_ok.argtypes = [dp, dp, i32, i32]
+    lib.kvc_admission_ok.restype = i32
+    lib.kvc_admission_min_buffered.argtypes = [dp, dp, i32]
+    lib.kvc_admission_min_buffered.restype = i32
     if path is None:
         _lib = lib
     return lib
@@ -126,3 +143,74 @@ def kvc_fetch_pipeline(layout, chunks, staging_ptrs, staging_bytes, layer_cache_
                                      copy_stream, compute_stream, C.byref(ms) if timed else None),
            "kvc_fetch_pipeline")
     return ms.value if timed else None
+
+
+def frame_size(layout):
+    return load().kvc_frame_size(C.byref(layout))
+
+
+def frame_offset(layout, kind, layer_group, frame_index):
+    return load().kvc_frame_offset(C.byref(layout), kind, layer_group, frame_index)
+
+
+def kvc_restore_paged_frame(layout, frame_ptr, meta_ptr, kind, layer_group, frame_index, first_token, n_tokens,
+                            layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr, table_len, err_ptr=None,
+                            stream=0):
+    _check(load().kvc_restore_paged_frame(C.byref(layout), frame_ptr, meta_ptr, kind, layer_group, frame_index,
+                                          first_token, n_tokens, layer_cache_ptrs_dev, num_blocks, block_size,
+                                          block_table_ptr, table_len, err_ptr, stream), "kvc_restore_paged_frame")
+
+
+def kvc_restore_paged_frames(layout, frames_ptr, meta_ptr, first_frame, n_frames, first_token, n_tokens,
+                             layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr, table_len, err_ptr=None,
+                             stream=0):
+    _check(load().kvc_restore_paged_frames(C.byref(layout), frames_ptr, meta_ptr, first_frame, n_frames, first_token,
+                                           n_tokens, layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr,
+                                           table_len, err_ptr, stream), "kvc_restore_paged_frames")
+
+
+def meta_staging_size(layout, order):
+    return load().kvc_meta_staging_size(C.byref(layout), order)
+
+
+def kvc_fetch_pipeline_frames(layout, chunks, frame_staging_ptrs, frame_staging_bytes, meta_staging_ptrs,
+                              meta_staging_bytes, layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr,
+                              table_len, err_ptr, copy_stream, compute_stream, order=KVC_ORDER_CHUNK,
+                              group_ready_events=None, timed=True, group_times=False):
+    """chunks: list of (host_ptr, bytes, n_tokens); group_ready_events: list of LG hipEvent_t handles or None.
+    Returns fetch-to-ready ms when timed (with the list of per-layer-group ready times when group_times), else None."""
+    arr = (HostChunk * len(chunks))(*[HostChunk(p, b, n) for p, b, n in chunks])
+    fs = (C.c_void_p * len(frame_staging_ptrs))(*frame_staging_ptrs)
+    ms_ = (C.c_void_p * len(meta_staging_ptrs))(*meta_staging_ptrs)
+    ev = (C.c_void_p * len(group_ready_events))(*group_ready_events) if group_ready_events is not None else None
+    LG = (layout.num_layers + 2) // 3
+    ms = C.c_float(0.0)
+    gms = (C.c_float * max(LG, 1))() if group_times else None
+    _check(load().kvc_fetch_pipeline_frames(C.byref(layout), arr, len(chunks), fs, frame_staging_bytes,
+                                            len(frame_staging_ptrs), ms_, meta_staging_bytes, len(meta_staging_ptrs),
+                                            layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr, table_len,
+                                            err_ptr, copy_stream, compute_stream, order, ev, gms,
+                                            C.byref(ms) if timed else None),
+           "kvc_fetch_pipeline_frames")
+    if group_times:
+        return (ms.value if timed else None), [gms[i] for i in range(LG)]
+    return ms.value if timed else None
+
+
+def _doubles(xs):
+    return (C.c_double * len(xs))(*[float(x) for x in xs])
+
+
+def admission_ok(t_fetch, t_comp, n_buffered):
+    """Appx A.3 non-blocking condition; 1 / 0, or -1 on a bad argument."""
+    n = len(t_fetch)
+    if len(t_comp) != n:
+        return -1
+    return load().kvc_admission_ok(_doubles(t_fetch), _doubles(t_comp), n, n_buffered)
+
+
+def admission_min_buffered(t_fetch, t_comp):
+    n = len(t_fetch)
+    if len(t_comp) != n:
+        return -1
+    return load().kvc_admission_min_buffered(_doubles(t_fetch), _doubles(t_comp), n)

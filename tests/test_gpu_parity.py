@@ -315,3 +315,209 @@ def test_config_pipeline_matches_single_call():
     for l in (0, 13, w.L - 1):
         got = ref.layers[l][:, phys.cuda()].cpu().numpy().view(np.uint16)
         hz.assert_same_bytes(f"pipeline chunk {c} layer {l}", got, want_caches[l].reshape(2, n_logical, bs, C)[:, phys.numpy()])
+
+
+# ------------------------------------------------------------------ frame-wise restoration
+
+
+def gpu_restore_frame(glo, frame, meta, kind, lg, f, first_token, n_tokens, cache, table):
+    hz.kvc.kvc_restore_paged_frame(glo, frame.data_ptr(), meta.data_ptr(), kind, lg, f, first_token, n_tokens,
+                                   cache.ptrs.data_ptr(), cache.num_blocks, cache.block_size, table.data_ptr(),
+                                   table.numel(), cache.err.data_ptr(), hz.stream_handle())
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [SMALL[0], SMALL[2], SMALL[4], SMALL[6]], ids=["s0", "s2", "s4", "s6"])
+def test_frame_restore_each_frame_against_oracle(shape, dtype):
+    """Every frame of every chunk through kvc_restore_paged_frame into its own poison cache == the oracle's frame
+    restore (bit-exact, poison included); all frames into one cache == the chunk-level call."""
+    L, H, D, T, th, tw, TX, TY, n, bs = shape
+    glo, olo = hz.layouts(L, H, D, dtype, T, th, tw, TX, TY)
+    C = H * D
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=77 + L, device="cuda")
+    frames, meta = hz.gpu_pack(glo, kv, n)
+    fb, mb, F = hz.kvc.chunk_sizes(glo)
+    fs = hz.kvc.frame_size(glo)
+    LG = (L + 2) // 3
+    assert fs == oracle.frame_size(olo) and fb == 2 * LG * F * fs
+    n_logical = (n + bs - 1) // bs
+    nb = n_logical + 2
+    table = kv_synth.make_block_table(n_logical, nb, 4)
+    tab = table.cuda()
+    f_np, m_np = frames.cpu().numpy(), meta.cpu().numpy()
+    union = hz.PagedCache(L, nb, bs, C)
+    for c in range((n + T - 1) // T):
+        nt = min(T, n - c * T)
+        meta_c = meta[c * mb // 4:(c + 1) * mb // 4]
+        for kind, lg, f in itertools.product((0, 1), range(LG), range(F)):
+            off = hz.kvc.frame_offset(glo, kind, lg, f)
+            assert off == oracle.frame_start(olo, kind, lg, f)
+            frame = frames[c * fb + off: c * fb + off + fs]
+            one = hz.PagedCache(L, nb, bs, C)
+            gpu_restore_frame(glo, frame, meta_c, kind, lg, f, c * T, nt, one, tab)
+            gpu_restore_frame(glo, frame, meta_c, kind, lg, f, c * T, nt, union, tab)
+            torch.cuda.synchronize()
+            want = [np.full(2 * nb * bs * C, hz.POISON, dtype=np.uint16) for _ in range(L)]
+            err = oracle.restore_paged_frame(olo, f_np[c * fb + off: c * fb + off + fs], m_np[c * mb // 4:(c + 1) * mb // 4],
+                                             kind, lg, f, c * T, nt, want, nb, bs, table.numpy())
+            assert err == 0 and int(one.err.item()) == 0
+            for l, (got, w) in enumerate(zip(one.numpy_layers(), want)):
+                hz.assert_same_bytes(f"chunk {c} frame ({kind},{lg},{f}) layer {l}", got, w)
+    ref = hz.PagedCache(L, nb, bs, C)
+    hz.gpu_restore_paged(glo, frames, meta, 0, n, ref, tab)
+    for l in range(L):
+        assert torch.equal(union.layers[l], ref.layers[l])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [SMALL[1], SMALL[3], SMALL[5], SMALL[6]], ids=["s1", "s3", "s5", "s6"])
+def test_frame_ranges_and_small_frame_pipeline(shape, dtype):
+    """Runs of consecutive frames in one launch (random cuts of each chunk's frame sequence) and the frame pipeline
+    in both orders with slots of one, a few and all frames, ragged last chunk included: same cache as the
+    chunk-level call."""
+    L, H, D, T, th, tw, TX, TY, n, bs = shape
+    glo, olo = hz.layouts(L, H, D, dtype, T, th, tw, TX, TY)
+    C = H * D
+    kvc = hz.kvc
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=99 + n, device="cuda")
+    frames, meta = hz.gpu_pack(glo, kv, n)
+    fb, mb, F = kvc.chunk_sizes(glo)
+    fs = kvc.frame_size(glo)
+    per_chunk = fb // fs
+    n_chunks = (n + T - 1) // T
+    n_logical = (n_chunks * T + bs - 1) // bs
+    nb = n_logical + 1
+    tab = kv_synth.make_block_table(n_logical, nb, 8).cuda()
+    ref = hz.PagedCache(L, nb, bs, C)
+    hz.gpu_restore_paged(glo, frames, meta, 0, n, ref, tab)
+    rng = np.random.default_rng(n)
+    got = hz.PagedCache(L, nb, bs, C)
+    for c in range(n_chunks):
+        nt = min(T, n - c * T)
+        cuts = sorted(set(rng.integers(1, per_chunk, size=3).tolist())) if per_chunk > 1 else []
+        for a, b in zip([0] + cuts, cuts + [per_chunk]):
+            kvc.kvc_restore_paged_frames(glo, frames[c * fb + a * fs:].data_ptr(), meta[c * mb // 4:].data_ptr(), a, b - a,
+                                         c * T, nt, got.ptrs.data_ptr(), nb, bs, tab.data_ptr(), tab.numel(),
+                                         got.err.data_ptr(), hz.stream_handle())
+    torch.cuda.synchronize()
+    assert int(got.err.item()) == 0
+    for l in range(L):
+        assert torch.equal(got.layers[l], ref.layers[l]), f"frame ranges: layer {l}"
+    moff = kvc.blob_meta_offset(glo)
+    blob_bytes = moff + mb
+    blobs = []
+    for c in range(n_chunks):
+        b = torch.zeros(blob_bytes, dtype=torch.uint8, pin_memory=True)
+        b[:fb].copy_(frames[c * fb:(c + 1) * fb])
+        b[moff:moff + mb].copy_(meta.view(torch.uint8)[c * mb:(c + 1) * mb])
+        blobs.append(b)
+    chunks = [(b.data_ptr(), blob_bytes, min(T, n - c * T)) for c, b in enumerate(blobs)]
+    s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    LG = (L + 2) // 3
+    for order in (kvc.KVC_ORDER_CHUNK, kvc.KVC_ORDER_LAYER):
+        msz = kvc.meta_staging_size(glo, order)
+        for per_slot, n_fs, n_ms in ((1, 2, 2), (3, 3, 2), (2 * F + 1, 2, 3), (per_chunk + 2, 2, 2)):
+            cache = hz.PagedCache(L, nb, bs, C)
+            fstage = [torch.empty(per_slot * fs + 256, dtype=torch.uint8, device="cuda") for _ in range(n_fs)]
+            mstage = [torch.full((msz + 256,), 0xEE, dtype=torch.uint8, device="cuda") for _ in range(n_ms)]
+            torch.cuda.synchronize()
+            ms, gms = kvc.kvc_fetch_pipeline_frames(glo, chunks, [s.data_ptr() for s in fstage], per_slot * fs + 255,
+                                                    [s.data_ptr() for s in mstage], msz, cache.ptrs.data_ptr(), nb, bs,
+                                                    tab.data_ptr(), tab.numel(), cache.err.data_ptr(),
+                                                    s_copy.cuda_stream, s_comp.cuda_stream, order=order, timed=True,
+                                                    group_times=True)
+            torch.cuda.synchronize()
+            assert ms > 0 and int(cache.err.item()) == 0
+            assert len(gms) == LG and all(0 < t <= ms + 1e-3 for t in gms) and gms == sorted(gms)
+            for l in range(L):
+                assert torch.equal(cache.layers[l], ref.layers[l]), f"order {order} per_slot={per_slot}: layer {l}"
+            for m in mstage:  # nothing written behind the stated meta staging size
+                assert bool((m[msz:] == 0xEE).all())
+
+
+def test_frame_restore_bad_block_ids():
+    L, H, D, T, n, bs = 3, 8, 128, 64, 64, 16
+    glo, olo = hz.layouts(L, H, D, "f16", T, 8, 128, 4, 4)
+    kv = kv_synth.make_kv(L, H, D, n, torch.float16, seed=3, device="cuda")
+    frames, meta = hz.gpu_pack(glo, kv, n)
+    fs = hz.kvc.frame_size(glo)
+    table = torch.tensor([2, 99, 0, -5], dtype=torch.int32)
+    cache = hz.PagedCache(L, 4, bs, H * D)
+    gpu_restore_frame(glo, frames[:fs], meta, 0, 0, 0, 0, n, cache, table.cuda())
+    torch.cuda.synchronize()
+    want = [np.full(2 * 4 * bs * H * D, hz.POISON, dtype=np.uint16) for _ in range(L)]
+    err = oracle.restore_paged_frame(olo, frames[:fs].cpu().numpy(), meta.cpu().numpy(), 0, 0, 0, 0, n, want, 4, bs, table.numpy())
+    assert err == 1 and int(cache.err.item()) == 1
+    for l, (got, w) in enumerate(zip(cache.numpy_layers(), want)):
+        hz.assert_same_bytes(f"layer {l}", got, w)
+
+
+def test_config_frame_pipeline_matches_chunk_restore():
+    """Benchmark pipeline workload at frame granularity: a few frame-sized staging slots instead of chunk blobs."""
+    w = kv_synth.WORKLOADS["llama3_8b_32k_pipeline"]
+    glo, olo = hz.workload_layouts(w)
+    C, T, bs = w.C, w.T, w.block_size
+    kvc = hz.kvc
+    kv = kv_synth.make_workload_kv(w, "cuda")
+    frames, meta = hz.gpu_pack(glo, kv, w.n_tokens)
+    del kv
+    fb, mb, _ = kvc.chunk_sizes(glo)
+    moff = kvc.blob_meta_offset(glo)
+    blob_bytes = moff + mb
+    blobs = []
+    for c in range(w.n_chunks):
+        b = torch.zeros(blob_bytes, dtype=torch.uint8, pin_memory=True)
+        b[:fb].copy_(frames[c * fb:(c + 1) * fb])
+        b[moff:moff + mb].copy_(meta.view(torch.uint8)[c * mb:(c + 1) * mb])
+        blobs.append(b)
+    n_logical = w.n_logical_blocks
+    table = kv_synth.make_block_table(n_logical, n_logical, w.seed).cuda()
+    ref = hz.PagedCache(w.L, n_logical, bs, C)
+    hz.gpu_restore_paged(glo, frames, meta, 0, w.n_tokens, ref, table)
+    fs = kvc.frame_size(glo)
+    assert fs == 1_572_864
+    LG = (w.L + 2) // 3
+    for order, per_slot, n_fs, n_ms in ((0, 1, 2, 2), (0, 16, 3, 3), (1, 4, 3, 2), (1, 16, 3, 4)):
+        cache = hz.PagedCache(w.L, n_logical, bs, C)
+        msz = kvc.meta_staging_size(glo, order)
+        fstage = [torch.empty(per_slot * fs, dtype=torch.uint8, device="cuda") for _ in range(n_fs)]
+        mstage = [torch.empty(msz, dtype=torch.uint8, device="cuda") for _ in range(n_ms)]
+        s_copy, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        ms, gms = kvc.kvc_fetch_pipeline_frames(glo, [(b.data_ptr(), blob_bytes, T) for b in blobs],
+                                                [s.data_ptr() for s in fstage], per_slot * fs,
+                                                [s.data_ptr() for s in mstage], msz,
+                                                cache.ptrs.data_ptr(), n_logical, bs, table.data_ptr(), n_logical,
+                                                cache.err.data_ptr(), s_copy.cuda_stream, s_comp.cuda_stream,
+                                                order=order, timed=True, group_times=True)
+        torch.cuda.synchronize()
+        hz.say(f"[case] frame pipeline order={order}, {n_fs} slots of {per_slot} frames, {n_ms} meta slots: "
+               f"fetch-to-ready {ms:.2f} ms, first/last group ready {gms[0]:.2f}/{gms[-1]:.2f} ms, "
+               f"staging {(n_fs * per_slot * fs + n_ms * msz) / 2**20:.1f} MiB")
+        assert ms > 0 and int(cache.err.item()) == 0
+        assert gms == sorted(gms) and gms[-1] <= ms + 1e-3
+        if order == kvc.KVC_ORDER_LAYER:
+            assert gms[0] < ms / 4   # the first of 11 groups is ready long before the last
+        else:
+            assert gms[0] > ms / 2   # chunk order completes every group only in the last of 16 chunks
+        for l in range(w.L):
+            assert torch.equal(cache.layers[l], ref.layers[l]), f"layer {l} differs from the chunk-level restore"
+    # caller-made events, call returns after enqueueing: once group g's event has fired its layers are complete
+    cache = hz.PagedCache(w.L, n_logical, bs, C)
+    events = [torch.cuda.Event() for _ in range(LG)]
+    for e in events:
+        e.record(s_comp)   # torch creates the underlying event at its first record
+    torch.cuda.synchronize()
+    r = kvc.kvc_fetch_pipeline_frames(glo, [(b.data_ptr(), blob_bytes, T) for b in blobs],
+                                      [s.data_ptr() for s in fstage], per_slot * fs, [s.data_ptr() for s in mstage], msz,
+                                      cache.ptrs.data_ptr(), n_logical, bs, table.data_ptr(), n_logical,
+                                      cache.err.data_ptr(), s_copy.cuda_stream, s_comp.cuda_stream,
+                                      order=kvc.KVC_ORDER_LAYER, group_ready_events=[e.cuda_event for e in events],
+                                      timed=False)
+    assert r is None
+    for g in (0, LG // 2, LG - 1):
+        events[g].synchronize()
+        for l in range(3 * g, min(3 * g + 3, w.L)):
+            assert torch.equal(cache.layers[l], ref.layers[l]), f"group {g} event fired before layer {l} was complete"
+    s_comp.synchronize()
+    torch.cuda.synchronize()

@@ -5,6 +5,8 @@ import ctypes
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 import paper_2602_09725_amd as kvc
@@ -25,6 +27,8 @@ def test_library_exports_every_declared_symbol(kvc_lib):
     body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(kvc_[a-z_]+)\s*\(", body))
     assert {"kvc_pack", "kvc_restore", "kvc_restore_paged", "kvc_fetch_pipeline", "kvc_chunk_sizes",
+            "kvc_restore_paged_frame", "kvc_restore_paged_frames", "kvc_fetch_pipeline_frames",
+            "kvc_meta_staging_size", "kvc_admission_ok", "kvc_admission_min_buffered", "kvc_frame_size", "kvc_frame_offset",
             "kvc_layout_validate", "kvc_status_str", "kvc_blob_meta_offset"} <= names
     for n in names:
         assert hasattr(kvc_lib, n), f"libkvc.so does not export {n}"
@@ -111,6 +115,69 @@ def test_data_calls_reject_bad_arguments_before_enqueueing(kvc_lib):
     assert pipe(cs=0) == 1
     assert pipe(tl=10) == 1
     assert pipe(staging=[A, A + 8]) == 1                   # staging alignment
+
+
+def test_frame_calls_reject_bad_arguments(kvc_lib):
+    lo = good()
+    fb, mb, F = kvc.chunk_sizes(lo)
+    A = 0x7F0000000000
+    assert kvc.frame_size(lo) == 3 * 512 * 1024
+    assert kvc.frame_offset(lo, 0, 0, 0) == 0 and kvc.frame_offset(lo, 1, 10, 3) == fb - kvc.frame_size(lo)
+    bad = ctypes.c_size_t(-1).value
+    assert kvc.frame_offset(lo, 2, 0, 0) == bad and kvc.frame_offset(lo, 0, 11, 0) == bad and kvc.frame_offset(lo, 0, 0, 4) == bad
+
+    def status(fn, *a):
+        try:
+            fn(*a)
+        except kvc.KvcError as e:
+            return e.status
+        return 0
+
+    fr = lambda **k: status(kvc.kvc_restore_paged_frame, lo, k.get("frame", A), k.get("meta", A), k.get("kind", 0),
+                            k.get("lg", 0), k.get("f", 0), k.get("first", 0), k.get("n", 2048), A, 256, 16, A,
+                            k.get("tl", 256))
+    assert fr(kind=2) == 1 and fr(lg=11) == 1 and fr(f=4) == 1 and fr(f=-1) == 1
+    assert fr(first=7) == 1 and fr(n=0) == 1 and fr(n=2049) == 1 and fr(tl=100) == 1
+    assert fr(frame=None) == 1 and fr(meta=None) == 1 and fr(frame=A + 4) == 1
+    frs = lambda first, count: status(kvc.kvc_restore_paged_frames, lo, A, A, first, count, 0, 2048, A, 256, 16, A, 256)
+    assert frs(-1, 1) == 1 and frs(0, 0) == 1 and frs(88, 1) == 1 and frs(80, 9) == 1 and frs(0, 89) == 1
+    blob = kvc.blob_meta_offset(lo) + mb
+    chunks = [(A, blob, 2048)] * 2
+    fsz = kvc.frame_size(lo)
+    pipe = lambda **k: status(kvc.kvc_fetch_pipeline_frames, lo, k.get("chunks", chunks), k.get("fst", [A, A + 256]),
+                              k.get("fsb", fsz), k.get("mst", [A, A + 256]), k.get("msb", mb), A, 512, 16, A, 512, None,
+                              k.get("cs", 1), k.get("xs", 2), k.get("order", 0), k.get("ev", None))
+    assert pipe(fst=[A]) == 1 and pipe(mst=[A]) == 1
+    assert pipe(fsb=fsz - 1) == 3 and pipe(msb=mb - 1) == 3
+    assert pipe(chunks=[(A, blob - 1, 2048)]) == 3
+    assert pipe(cs=3, xs=3) == 1 and pipe(fst=[A, A + 8]) == 1
+    assert pipe(order=2) == 1 and pipe(order=-1) == 1
+    assert pipe(ev=[A] * 10 + [None]) == 1
+    # meta staging: a chunk section, or the pairs of three layers (K per channel, V per token and head)
+    assert kvc.meta_staging_size(lo, kvc.KVC_ORDER_CHUNK) == mb
+    slice_bytes = 3 * (8 * 128 + 2048 * 8) * 8
+    assert kvc.meta_staging_size(lo, kvc.KVC_ORDER_LAYER) == slice_bytes
+    assert kvc.meta_staging_size(lo, 2) == bad
+    assert pipe(order=1, msb=slice_bytes - 1) == 3
+
+
+def test_admission_matches_oracle(kvc_lib):
+    """Appx A.3 condition: the library's running-sum form against the oracle's one-inequality-per-stage form."""
+    from oracle import admission
+    rng = np.random.default_rng(11)
+    for case in range(300):
+        n = int(rng.integers(1, 40))
+        if case % 3 == 0:      # integer times: ties (equality) are hit often
+            f, c = rng.integers(0, 4, n).tolist(), rng.integers(0, 5, n).tolist()
+        else:
+            f, c = rng.uniform(0, 1, n).tolist(), rng.uniform(0, 1.6, n).tolist()
+        assert kvc.admission_min_buffered(f, c) == admission.min_buffered(f, c)
+        for b in range(n + 1):
+            assert kvc.admission_ok(f, c, b) == int(admission.condition_holds(f, c, b))
+    assert kvc.admission_ok([1.0], [1.0], 2) == -1 and kvc.admission_ok([1.0], [1.0], -1) == -1
+    assert kvc.admission_ok([-1.0], [1.0], 0) == -1 and kvc.admission_ok([1.0], [float("nan")], 0) == -1
+    assert kvc.admission_min_buffered([float("inf")], [1.0]) == -1 and kvc.admission_min_buffered([], []) == -1
+    assert kvc.load().kvc_admission_ok(None, None, 1, 0) == -1
 
 
 def test_status_strings(kvc_lib):

@@ -475,3 +475,107 @@ def test_oracle_rejects_bad_arguments(oracle):
         oracle.restore_paged(lo, frames, meta, 3, 4, caches, 2, 4, np.arange(2))
     with pytest.raises(ValueError):  # table too short: 1 block of 4 slots for 5 tokens
         oracle.restore_paged(lo, frames, meta, 0, 5, caches, 2, 4, np.arange(1))
+
+
+# ------------------------------------------------------------------ frame-wise restoration
+
+
+def test_frame_restore_writes_exactly_its_tokens_and_layers(oracle):
+    """Sec. 3.3.2 + Sec. 3.2.1 step 3: one frame (kind, lg, f) carries the tokens t % F == f of layers 3lg..3lg+2;
+    everything else in the cache stays poison, and the written values are those of the chunk-level restore."""
+    lo = small_layout(oracle, L=5, T=22)  # LG = 2 (second group has 2 layers), F = 4, short second chunk
+    n = 22 + 9
+    bs, nb = 4, 11
+    C = lo.H * lo.D
+    F = oracle.frames_per_group(lo)
+    kv = rand_kv(lo, n, seed=21)
+    frames, meta = oracle.pack(lo, kv_synth.to_u16(kv), n)
+    fb, mf, fs = oracle.frame_bytes(lo), oracle.meta_floats(lo), oracle.frame_size(lo)
+    assert fb == 2 * 2 * F * fs
+    table = kv_synth.make_block_table((n + bs - 1) // bs, nb, seed=2).numpy()
+    whole = [np.full(2 * nb * bs * C, 0xDEAD, dtype=np.uint16) for _ in range(lo.L)]
+    oracle.restore_paged(lo, frames, meta, 0, n, whole, nb, bs, table)
+    union = [np.full(2 * nb * bs * C, 0xDEAD, dtype=np.uint16) for _ in range(lo.L)]
+    for c, nt in ((0, 22), (1, 9)):
+        for kind, lg, f in itertools.product((0, 1), (0, 1), range(F)):
+            start = oracle.frame_start(lo, kind, lg, f)
+            assert start == ((kind * 2 + lg) * F + f) * fs  # frames are laid out [kind][lg][f]
+            frame = frames[c * fb + start: c * fb + start + fs]
+            one = [np.full(2 * nb * bs * C, 0xDEAD, dtype=np.uint16) for _ in range(lo.L)]
+            err = oracle.restore_paged_frame(lo, frame, meta[c * mf:(c + 1) * mf], kind, lg, f, c * lo.T, nt, one, nb, bs, table)
+            assert err == 0
+            oracle.restore_paged_frame(lo, frame, meta[c * mf:(c + 1) * mf], kind, lg, f, c * lo.T, nt, union, nb, bs, table)
+            for l in range(lo.L):
+                got = one[l].reshape(2, nb, bs, C)
+                ref = whole[l].reshape(2, nb, bs, C)
+                for k2 in (0, 1):
+                    for p in range(nb * bs):
+                        blk, slot = divmod(p, bs)
+                        # which sequence position lives here?
+                        logical = np.flatnonzero(table == blk)
+                        pos = logical[0] * bs + slot if logical.size else -1
+                        t = pos - c * lo.T
+                        mine = (k2 == kind and l // 3 == lg and 0 <= t < nt and t % F == f and pos >= 0)
+                        if mine:
+                            assert np.array_equal(got[k2, blk, slot], ref[k2, blk, slot])
+                            assert (got[k2, blk, slot] != 0xDEAD).any()
+                        else:
+                            assert (got[k2, blk, slot] == 0xDEAD).all()
+    for l in range(lo.L):  # all frames together == the chunk-level restore
+        assert np.array_equal(union[l], whole[l])
+
+
+def test_frame_restore_rejects_bad_arguments(oracle):
+    lo = small_layout(oracle)
+    kv = kv_synth.to_u16(rand_kv(lo, 8)).reshape(-1)
+    frames, meta = oracle.pack(lo, kv, 8)
+    fs = oracle.frame_size(lo)
+    caches = [np.zeros(2 * 2 * 4 * lo.H * lo.D, dtype=np.uint16) for _ in range(lo.L)]
+    for kind, lg, f in ((2, 0, 0), (0, 2, 0), (0, 0, 4), (0, -1, 0)):
+        with pytest.raises(ValueError):
+            oracle.restore_paged_frame(lo, frames[:fs], meta, kind, lg, f, 0, 8, caches, 2, 4, np.arange(2))
+
+
+# ------------------------------------------------------------------ Appx A.3 admission condition
+
+
+def test_admission_uniform_times_closed_form():
+    """Uniform stage times d (fetch) and c (compute), 0 < d < c: stage k violates k*d <= (k-1)*c iff k < c/(c-d),
+    so the stages that must be buffered first are 1 .. ceil(c/(c-d)) - 1 (all n when that exceeds n)."""
+    from oracle import admission
+    for d, c, n in [(1, 2, 8), (3, 4, 8), (5, 7, 8), (3, 4, 2), (9, 10, 32), (1, 100, 5)]:
+        want = min(n, -(-c // (c - d)) - 1)
+        assert admission.min_buffered([d] * n, [c] * n) == want, (d, c, n)
+        for b in range(n + 1):
+            assert admission.condition_holds([d] * n, [c] * n, b) == (b >= want)
+    # fetch never faster than compute: nothing can be hidden; free fetch: nothing to hide
+    assert admission.min_buffered([2.0] * 6, [2.0] * 6) == 6
+    assert admission.min_buffered([3.0] * 6, [2.0] * 6) == 6
+    assert admission.min_buffered([0.0] * 6, [2.0] * 6) == 0
+    assert admission.min_buffered([0.0] * 6, [0.0] * 6) == 0  # 0 <= 0 holds: the bound is not strict
+
+
+def test_admission_hand_evaluated_example():
+    """Four stages, checked by hand: prefix sums of fetch 2,3,4,5 against shifted prefix sums of compute 0,4,5,6."""
+    from oracle import admission
+    f, c = [2, 1, 1, 1], [4, 1, 1, 9]
+    assert not admission.condition_holds(f, c, 0)      # k = 1: 2 <= 0 fails
+    assert admission.condition_holds(f, c, 1)          # k = 2..4: 3 <= 4, 4 <= 5, 5 <= 6
+    assert admission.min_buffered(f, c) == 1
+    f2 = [2, 1, 1, 3]                                   # k = 4: 7 <= 6 fails
+    assert not admission.condition_holds(f2, c, 3) and admission.condition_holds(f2, c, 4)
+    assert admission.min_buffered(f2, c) == 4
+    # the compute time of the last stage never enters: nothing is fetched behind it
+    assert admission.min_buffered(f, [4, 1, 1, 0]) == 1
+
+
+def test_admission_monotone_and_empty_constraint_set():
+    from oracle import admission
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(1, 12))
+        f, c = rng.uniform(0, 2, n).tolist(), rng.uniform(0, 3, n).tolist()
+        holds = [admission.condition_holds(f, c, b) for b in range(n + 1)]
+        assert holds[n]                                 # everything buffered: no inequality left
+        assert holds == sorted(holds)                   # once it holds it keeps holding
+        assert admission.min_buffered(f, c) == holds.index(True)
