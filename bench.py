@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # (scaled by what the counters read for a plain copy of known size), keyed by a hash of the kernel
 # sources they were taken with: once the kernels change the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "290bbfc689960669": {"pack": 6_825_627_648, "restore": 6_513_944_576},
+    "ac1f31805a292d55": {"pack": 6_824_657_306, "restore": 6_513_977_958},
 }
 
 
@@ -37,7 +37,8 @@ def kernel_source_hash():
     h = hashlib.sha256()
     here = os.path.dirname(os.path.abspath(__file__))
     for f in sorted(glob.glob(os.path.join(here, "paper_2602_09725_amd", "csrc", "*"))):
-        h.update(open(f, "rb").read())
+        if os.path.basename(f) != "kvc_api.hip":  # host code only: argument checks and the stream pipelines
+            h.update(open(f, "rb").read())
     return h.hexdigest()[:16]
 
 
