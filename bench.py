@@ -60,6 +60,7 @@ def main():
     ap.add_argument("--workload", default="llama3_8b_32k_paged")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-fetch", action="store_true")
+    ap.add_argument("--skip-resolutions", action="store_true")
     ap.add_argument("--cpu-sample-chunks", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -235,6 +236,37 @@ def main():
         out["fetch_frames"] = {"frame_bytes": fsz, "frames": len(blobs) * (fb // fsz),
                                "chunk_staging_MiB": round(n_staging * blob_bytes / 2**20, 1), "legs": legs}
         del blobs, staging
+
+    # ---- the same cache at the paper's four resolutions (Sec. 3.3.1): frame bytes and kernel times per version,
+    #      i.e. the profile table an adaptive-resolution selector (Alg. 1) would use on this pipeline
+    if not args.skip_resolutions:
+        rows = []
+        for name, (wd, ht) in (("240P", (426, 240)), ("480P", (854, 480)), ("640P", (1138, 640)), ("1080P", (1920, 1080))):
+            rlo = kvc.Layout(w.L, w.H, w.D, dt, w.T, w.th, w.tw, 1, 1)
+            if kvc.layout_set_resolution(rlo, wd, ht) != 0:
+                continue
+            rfb, rmb, rF = kvc.chunk_sizes(rlo)
+            rframes = torch.empty(w.n_chunks * rfb, dtype=torch.uint8, device=dev)
+            rmeta = torch.empty(w.n_chunks * rmb, dtype=torch.uint8, device=dev)
+            tp, tr = [], []
+            for it in range(6):
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+                e[0].record(stream)
+                kvc.kvc_pack(rlo, kv.data_ptr(), strides, w.n_tokens, rframes.data_ptr(), rframes.numel(),
+                             rmeta.data_ptr(), rmeta.numel(), stream.cuda_stream)
+                e[1].record(stream)
+                kvc.kvc_restore_paged(rlo, rframes.data_ptr(), rmeta.data_ptr(), 0, w.n_tokens, ptrs.data_ptr(), n_logical,
+                                      bs, table.data_ptr(), n_logical, err.data_ptr(), stream.cuda_stream)
+                e[2].record(stream)
+                torch.cuda.synchronize()
+                if it >= 2:
+                    tp.append(e[0].elapsed_time(e[1]))
+                    tr.append(e[1].elapsed_time(e[2]))
+            rows.append({"resolution": name, "tile_grid": [rlo.tiles_x, rlo.tiles_y], "frames_per_group": rF,
+                         "frame_bytes_per_chunk": rfb, "pack_ms": round(statistics.mean(tp), 4),
+                         "restore_ms": round(statistics.mean(tr), 4)})
+            del rframes, rmeta
+        out["resolutions"] = rows
 
     # ---- the CPU oracle on a bounded sample of the same workload (rank 0, N = 1)
     if not args.skip_cpu_baseline:

@@ -299,6 +299,36 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
 int32_t kvc_admission_ok(const double* t_fetch, const double* t_comp, int32_t n_stages, int32_t n_buffered);
 int32_t kvc_admission_min_buffered(const double* t_fetch, const double* t_comp, int32_t n_stages);
 
+/* Adaptive-resolution selector (Alg. 1, Appx A.2; Sec. 3.3.1), host arithmetic
+ * only.  For every resolution r of the supported set, in index order:
+ *   tau_trans = size[r] / bandwidth
+ *   tau_dec   = latency[(pool_load - 1) * n_res + r]      (profile table, one row per pool load)
+ *   tau_pen   = penalty[r] if active_res >= 0 and r != active_res, else 0
+ *   bubble    = | tau_trans - tau_dec - tau_pen |
+ * and the first r with the smallest bubble is returned (a later r replaces the
+ * kept one only on a strictly smaller bubble); *bubble (may be NULL) gets that
+ * bubble.  size and bandwidth share a unit (bytes and bytes/s, MB and MB/s, ...).
+ *   pool_load   present load of the decode pool, 1..n_loads
+ *   active_res  resolution the pool is working on, or -1 for an idle pool
+ * Returns -1 on a bad argument (NULL, n_res < 1, n_loads < 1, pool_load or
+ * active_res out of range, bandwidth not finite or <= 0, a negative or
+ * non-finite table entry). */
+int32_t kvc_select_resolution(const double* size, const double* latency, const double* penalty, int32_t n_res,
+                              int32_t n_loads, int32_t pool_load, int32_t active_res, double bandwidth,
+                              double* bubble);
+
+/* Bandwidth predictor of Sec. 3.3.1: size of the last chunk over its transmission
+ * delay.  Returns -1 unless both are finite and > 0. */
+double kvc_est_bandwidth(double last_chunk_size, double last_transmission_delay);
+
+/* A resolution is a tile grid (Sec. 3.2.1 step 2, Sec. 3.3.1: changing the
+ * tensor-to-frame layout changes the frame size).  Sets tiles_x = width / tile_w
+ * and tiles_y = height / tile_h (integer division, at least 1 each) in *layout,
+ * so that a frame is the largest whole-tile picture inside width x height pixels,
+ * and validates the result.  The same KV packed under two such layouts restores
+ * to the same tensors. */
+kvc_status kvc_layout_set_resolution(kvc_layout* layout, int32_t width, int32_t height);
+
 /* Static, never-freed description of a status code. */
 const char* kvc_status_str(kvc_status status);
 

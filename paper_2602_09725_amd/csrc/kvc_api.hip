@@ -543,6 +543,45 @@ bool good_times(const double* t, int32_t n) {
 
 }  // namespace
 
+int32_t kvc_select_resolution(const double* size, const double* latency, const double* penalty, int32_t n_res,
+                              int32_t n_loads, int32_t pool_load, int32_t active_res, double bandwidth,
+                              double* bubble) {
+  if (!size || !latency || !penalty || n_res < 1 || n_loads < 1 || n_res > (1 << 20) || n_loads > (1 << 20)) return -1;
+  if (pool_load < 1 || pool_load > n_loads || active_res < -1 || active_res >= n_res) return -1;
+  if (!good_times(&bandwidth, 1) || bandwidth == 0.0) return -1;
+  const double* row = latency + (size_t)(pool_load - 1) * n_res;
+  if (!good_times(size, n_res) || !good_times(penalty, n_res) || !good_times(row, n_res)) return -1;
+  int32_t best = -1;
+  double best_bubble = 0.0;
+  for (int32_t r = 0; r < n_res; ++r) {
+    const double trans = size[r] / bandwidth;
+    const double pen = (active_res >= 0 && r != active_res) ? penalty[r] : 0.0;
+    double gap = trans - row[r] - pen;
+    if (gap < 0.0) gap = -gap;
+    if (best < 0 || gap < best_bubble) {
+      best = r;
+      best_bubble = gap;
+    }
+  }
+  if (bubble) *bubble = best_bubble;
+  return best;
+}
+
+double kvc_est_bandwidth(double last_chunk_size, double last_transmission_delay) {
+  if (!good_times(&last_chunk_size, 1) || !good_times(&last_transmission_delay, 1)) return -1.0;
+  if (last_chunk_size == 0.0 || last_transmission_delay == 0.0) return -1.0;
+  return last_chunk_size / last_transmission_delay;
+}
+
+kvc_status kvc_layout_set_resolution(kvc_layout* layout, int32_t width, int32_t height) {
+  if (!layout || width < 1 || height < 1) return KVC_ERR_INVALID_ARG;
+  if (layout->tile_w < 1 || layout->tile_h < 1) return KVC_ERR_INVALID_ARG;
+  const int32_t tx = width / layout->tile_w, ty = height / layout->tile_h;
+  layout->tiles_x = tx < 1 ? 1 : tx;
+  layout->tiles_y = ty < 1 ? 1 : ty;
+  return kvc_layout_validate(layout);
+}
+
 int32_t kvc_admission_min_buffered(const double* t_fetch, const double* t_comp, int32_t n_stages) {
   if (!t_fetch || !t_comp || n_stages < 1 || !good_times(t_fetch, n_stages) || !good_times(t_comp, n_stages)) return -1;
   // The condition for k does not depend on n_buffered, so the answer is the largest k that violates it.

@@ -82,6 +82,11 @@ def load(path=None):
     lib.kvc_meta_staging_size.argtypes = [LP, i32]
     lib.kvc_meta_staging_size.restype = sz
     dp = C.POINTER(C.c_double)
+    lib.kvc_select_resolution.argtypes = [dp, dp, dp, i32, i32, i32, i32, C.c_double, dp]
+    lib.kvc_select_resolution.restype = i32
+    lib.kvc_est_bandwidth.argtypes = [C.c_double, C.c_double]
+    lib.kvc_est_bandwidth.restype = C.c_double
+    lib.kvc_layout_set_resolution.argtypes = [LP, i32, i32]
     lib.kvc_admission_ok.argtypes = [dp, dp, i32, i32]
     lib.kvc_admission_ok.restype = i32
     lib.kvc_admission_min_buffered.argtypes = [dp, dp, i32]
@@ -214,3 +219,24 @@ def admission_min_buffered(t_fetch, t_comp):
     if len(t_comp) != n:
         return -1
     return load().kvc_admission_min_buffered(_doubles(t_fetch), _doubles(t_comp), n)
+
+
+def select_resolution(sizes, latency_rows, penalty, pool_load, active_res, bandwidth):
+    """Alg. 1.  latency_rows[load - 1][r].  Returns (r_opt, bubble), or (-1, None) on a bad argument."""
+    n_res, n_loads = len(sizes), len(latency_rows)
+    if len(penalty) != n_res or any(len(row) != n_res for row in latency_rows):
+        return -1, None
+    flat = [x for row in latency_rows for x in row]
+    bubble = C.c_double(0.0)
+    r = load().kvc_select_resolution(_doubles(sizes), _doubles(flat), _doubles(penalty), n_res, n_loads, pool_load,
+                                     active_res, float(bandwidth), C.byref(bubble))
+    return (r, bubble.value) if r >= 0 else (-1, None)
+
+
+def est_bandwidth(last_chunk_size, last_transmission_delay):
+    return load().kvc_est_bandwidth(float(last_chunk_size), float(last_transmission_delay))
+
+
+def layout_set_resolution(layout, width, height):
+    """Sets the tile grid of `layout` for frames of at most width x height pixels; returns the status."""
+    return load().kvc_layout_set_resolution(C.byref(layout), width, height)

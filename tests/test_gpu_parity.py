@@ -78,6 +78,29 @@ def test_small_geometries(shape, modes, dtype):
     full_check(glo, olo, kv, n, dtype, block_size=bs, tag="small")
 
 
+PAPER_RESOLUTIONS = {"240P": (426, 240), "480P": (854, 480), "640P": (1138, 640), "1080P": (1920, 1080)}
+
+
+def test_multi_resolution_versions_of_one_cache():
+    """One KV cache packed at the paper's four resolutions (Sec. 3.2.1 step 2 / Sec. 3.3.1: a resolution is a tile
+    grid): each version bit-exact against the oracle, and all versions restore to the same tensors with the same
+    pairs, since the grid moves tiles around but never changes a quantization group."""
+    L, H, D, T, n, bs = 4, 8, 128, 2048, 2048 + 700, 16
+    kv = kv_synth.make_kv(L, H, D, n, torch.float16, seed=240480, device="cuda")
+    first = None
+    for name, (wd, ht) in PAPER_RESOLUTIONS.items():
+        glo, _ = hz.layouts(L, H, D, "f16", T, 8, 128, 1, 1)
+        assert hz.kvc.layout_set_resolution(glo, wd, ht) == 0
+        glo, olo = hz.layouts(L, H, D, "f16", T, 8, 128, glo.tiles_x, glo.tiles_y)
+        frames, meta = full_check(glo, olo, kv, n, "f16", block_size=bs, tag=f"resolution {name}")
+        out = hz.gpu_restore(glo, frames, meta, n, torch.float16)
+        if first is None:
+            first = (name, meta.clone(), out.clone())
+        else:
+            assert torch.equal(meta.view(torch.int32), first[1].view(torch.int32)), f"pairs of {name} != {first[0]}"
+            assert torch.equal(out.view(torch.int16), first[2].view(torch.int16)), f"{name} restores differently from {first[0]}"
+
+
 def adversarial_kv(L, H, D, n, dtype):
     """Values that stress the quantizer: constant groups, +-0, extremes, exact ties, subnormals, huge ranges."""
     g = torch.Generator().manual_seed(77)

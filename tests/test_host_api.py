@@ -28,7 +28,8 @@ def test_library_exports_every_declared_symbol(kvc_lib):
     names = set(re.findall(r"\b(kvc_[a-z_]+)\s*\(", body))
     assert {"kvc_pack", "kvc_restore", "kvc_restore_paged", "kvc_fetch_pipeline", "kvc_chunk_sizes",
             "kvc_restore_paged_frame", "kvc_restore_paged_frames", "kvc_fetch_pipeline_frames",
-            "kvc_meta_staging_size", "kvc_admission_ok", "kvc_admission_min_buffered", "kvc_frame_size", "kvc_frame_offset",
+            "kvc_meta_staging_size", "kvc_admission_ok", "kvc_admission_min_buffered", "kvc_select_resolution",
+            "kvc_est_bandwidth", "kvc_layout_set_resolution", "kvc_frame_size", "kvc_frame_offset",
             "kvc_layout_validate", "kvc_status_str", "kvc_blob_meta_offset"} <= names
     for n in names:
         assert hasattr(kvc_lib, n), f"libkvc.so does not export {n}"
@@ -189,3 +190,48 @@ def test_status_strings(kvc_lib):
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         binding.load(str(tmp_path / "libkvc.so"))
+
+
+def test_select_resolution_matches_oracle_and_the_papers_tables(kvc_lib):
+    """Alg. 1: the library against the oracle on random profile tables and on the hand-evaluated cases."""
+    from oracle import resolution
+    from test_oracle_pins import load_alg1_cases, load_alg1_tables
+    tables = load_alg1_tables()
+    for dev, load, active, bw, chosen, bubble in load_alg1_cases():
+        sizes, rows, pen = tables[dev]
+        r, b = kvc.select_resolution(sizes, rows, pen, load, active, bw)
+        assert r == chosen and abs(b - bubble) < 1e-8
+    rng = np.random.default_rng(21)
+    for case in range(300):
+        n, loads = int(rng.integers(1, 7)), int(rng.integers(1, 8))
+        if case % 3 == 0:   # small integers: exact ties and zero bubbles
+            sizes, lat, pen = rng.integers(1, 6, n) * 100.0, rng.integers(0, 6, (loads, n)) * 1.0, rng.integers(0, 2, n) * 1.0
+            bw = 100.0
+        else:
+            sizes, lat, pen = rng.uniform(50, 300, n), rng.uniform(0.05, 0.6, (loads, n)), rng.uniform(0, 0.1, n)
+            bw = float(rng.uniform(100, 2000))
+        load, active = int(rng.integers(1, loads + 1)), int(rng.integers(-1, n))
+        want = resolution.select_resolution(sizes, lat, pen, load, active, bw)
+        assert kvc.select_resolution(sizes.tolist(), lat.tolist(), pen.tolist(), load, active, bw) == want
+    s, l, p = [180.0, 256.0], [[0.2, 0.19]], [0.08, 0.0]
+    assert kvc.select_resolution(s, l, p, 0, 0, 100.0)[0] == -1 and kvc.select_resolution(s, l, p, 2, 0, 100.0)[0] == -1
+    assert kvc.select_resolution(s, l, p, 1, 2, 100.0)[0] == -1 and kvc.select_resolution(s, l, p, 1, -2, 100.0)[0] == -1
+    assert kvc.select_resolution(s, l, p, 1, 0, 0.0)[0] == -1 and kvc.select_resolution(s, l, p, 1, 0, float("nan"))[0] == -1
+    assert kvc.select_resolution([180.0, -1.0], l, p, 1, 0, 100.0)[0] == -1
+    assert kvc.select_resolution(s, [[0.2, float("inf")]], p, 1, 0, 100.0)[0] == -1
+    assert kvc.est_bandwidth(256e6, 0.5) == resolution.est_bandwidth(256e6, 0.5) == 512e6
+    assert kvc.est_bandwidth(1.0, 0.0) == -1.0 and kvc.est_bandwidth(-1.0, 1.0) == -1.0
+
+
+def test_layout_set_resolution(kvc_lib):
+    """The paper's four resolutions as tile grids of the (8,128) tile: whole tiles inside width x height."""
+    for (wd, ht), (tx, ty, F) in {(426, 240): (3, 30, 23), (854, 480): (6, 60, 6), (1138, 640): (8, 80, 4),
+                                  (1920, 1080): (15, 135, 2)}.items():
+        lo = good()
+        assert kvc.layout_set_resolution(lo, wd, ht) == 0
+        assert (lo.tiles_x, lo.tiles_y) == (tx, ty)
+        fb, mb, frames = kvc.chunk_sizes(lo)
+        assert frames == F and fb == 2 * 11 * F * 3 * (ty * 8) * (tx * 128)
+    lo = good()
+    assert kvc.layout_set_resolution(lo, 100, 4) == 0 and (lo.tiles_x, lo.tiles_y) == (1, 1)   # smaller than a tile
+    assert kvc.layout_set_resolution(lo, 0, 240) == 1 and kvc.layout_set_resolution(lo, 426, -1) == 1

@@ -579,3 +579,70 @@ def test_admission_monotone_and_empty_constraint_set():
         assert holds[n]                                 # everything buffered: no inequality left
         assert holds == sorted(holds)                   # once it holds it keeps holding
         assert admission.min_buffered(f, c) == holds.index(True)
+
+
+# ------------------------------------------------------------------ Alg. 1 adaptive-resolution selector
+
+
+def load_alg1_tables():
+    """{device: (sizes, latency rows by load, penalty)} from the tables the paper prints (Appx A.2)."""
+    tables = {}
+    for line in open(os.path.join(HERE, "golden", "alg1_lookup_tables.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        tok = line.split()
+        dev = tables.setdefault(tok[0], {"load": {}, "penalty": None, "size": None})
+        if tok[1] == "load":
+            dev["load"][int(tok[2])] = [float(x) for x in tok[3:]]
+        else:
+            dev[tok[1]] = [float(x) for x in tok[2:]]
+    out = {}
+    for name, d in tables.items():
+        rows = [d["load"][k] for k in range(1, len(d["load"]) + 1)]
+        out[name] = (d["size"], rows, d["penalty"])
+    return out
+
+
+def load_alg1_cases():
+    cases = []
+    for line in open(os.path.join(HERE, "golden", "alg1_cases.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        dev, load, active, bw, chosen, bubble = line.split()
+        cases.append((dev, int(load), int(active), float(bw), int(chosen), float(bubble)))
+    return cases
+
+
+def test_alg1_hand_evaluated_selections_on_the_papers_tables():
+    from oracle import resolution
+    tables = load_alg1_tables()
+    assert set(tables) == {"H20", "L20", "A100"} and len(tables["H20"][1]) == 7
+    cases = load_alg1_cases()
+    assert len(cases) == 8
+    for dev, load, active, bw, chosen, bubble in cases:
+        sizes, rows, pen = tables[dev]
+        r, b = resolution.select_resolution(sizes, rows, pen, load, active, bw)
+        assert r == chosen, (dev, load, active, bw, r, b)
+        assert abs(b - bubble) < 1e-8
+
+
+def test_alg1_zero_bubble_ties_and_scaling():
+    from oracle import resolution
+    # a resolution whose transmission takes exactly as long as its decoding wins with bubble 0
+    r, b = resolution.select_resolution([100, 200, 400], [[3.0, 2.0, 5.0]], [0, 0, 0], 1, -1, 100.0)
+    assert (r, b) == (1, 0.0)
+    # equal bubbles: the earlier resolution of the set is kept
+    r, b = resolution.select_resolution([100, 300], [[2.0, 2.0]], [0, 0], 1, -1, 100.0)   # |1-2| = |3-2|
+    assert (r, b) == (0, 1.0)
+    # scaling every time by 4 (sizes x4 at the same bandwidth, latencies and penalties x4) changes no decision
+    rng = np.random.default_rng(3)
+    for _ in range(100):
+        n, loads = int(rng.integers(1, 6)), int(rng.integers(1, 5))
+        sizes = rng.uniform(50, 300, n)
+        lat = rng.uniform(0.05, 0.6, (loads, n))
+        pen = rng.uniform(0, 0.1, n)
+        load, active, bw = int(rng.integers(1, loads + 1)), int(rng.integers(-1, n)), float(rng.uniform(100, 2000))
+        r1, b1 = resolution.select_resolution(sizes, lat, pen, load, active, bw)
+        r2, b2 = resolution.select_resolution(sizes * 4, lat * 4, pen * 4, load, active, bw)
+        assert r1 == r2 and b2 == 4 * b1      # powers of two scale exactly in binary floating point
+    assert resolution.est_bandwidth(256e6, 0.5) == 512e6
