@@ -64,6 +64,7 @@ struct PackParams {
   int32_t strip_atoms;    // atoms (8 channels each) per strip, a power of two <= 16
   int32_t n_strips;
   int32_t rows;           // token rows per pass = threads / strip_atoms
+  uint32_t pass_step;     // bytes the code offset of a thread grows per pass, 0 if that is not a constant
   int32_t n_kinds_ch;
   int32_t resident;       // per-channel strips are held in registers (one read of the input)
   int32_t kinds_ch[2];

@@ -430,9 +430,9 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
   uint32_t r, cc;
   fd_divmod(g.dtw, e, r, cc);
   const uint32_t lg = l / 3u, pl = l - lg * 3u;
-  uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane +
-                   (r * (uint32_t)g.W + cc);
-  const uint16_t* src = p.kv + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts + e;
+  uint8_t* fplane = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane;
+  const uint8_t* srcb = reinterpret_cast<const uint8_t*>(p.kv + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts);
+  const uint32_t ts2 = (uint32_t)p.ts * 2u;
 
   u32x4 v[NI];
   float mnv[8], inv[8];
@@ -440,11 +440,12 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
   for (int i = 0; i < 8; ++i) mnv[i] = inv[i] = 0.f;
 
   if (n > 0) {
+    const uint32_t nm1 = (uint32_t)n - 1u;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const uint32_t t = row + (uint32_t)i * rows;
-      const uint32_t tc = t < (uint32_t)n ? t : (uint32_t)n - 1u;  // a repeated token leaves min / max unchanged
-      v[i] = stream_load<u32x4>(src + (int64_t)tc * p.ts);
+      // a repeated token leaves min / max unchanged
+      v[i] = stream_load<u32x4>(srcb + (size_t)(uint32_t)((t < nm1 ? t : nm1) * ts2 + e * 2u));
     }
     ColumnStats<DT> st;
     st.init();
@@ -463,25 +464,43 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
       }
     }
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float l0 = red_lo[0][a * 8 + i], h0 = red_hi[0][a * 8 + i];
+    // one thread per channel of the strip finishes the reduction and derives the group's parameters
+    float* par_mn = &red_lo[kMaxWaves][0];
+    float* par_inv = &red_hi[kMaxWaves][0];
+    if (tid < sa * 8u) {
+      float l0 = red_lo[0][tid], h0 = red_hi[0][tid];
       for (uint32_t w = 1; w < n_waves; ++w) {
-        l0 = __builtin_fminf(l0, red_lo[w][a * 8 + i]);
-        h0 = __builtin_fmaxf(h0, red_hi[w][a * 8 + i]);
+        l0 = __builtin_fminf(l0, red_lo[w][tid]);
+        h0 = __builtin_fmaxf(h0, red_hi[w][tid]);
       }
       const GroupParams q = group_params(l0, h0);
-      mnv[i] = q.mn;
-      inv[i] = q.inv;
-      if (row == 0 && active) {
-        float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + e + i);
+      par_mn[tid] = q.mn;
+      par_inv[tid] = q.inv;
+      const uint32_t ch = strip * sa * 8u + tid;
+      if (ch < (uint32_t)g.C) {
+        float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + ch);
         *reinterpret_cast<f32x2*>(mp) = f32x2{q.scale, q.mn};
       }
     }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      mnv[i] = par_mn[a * 8 + i];
+      inv[i] = par_inv[a * 8 + i];
+    }
   }
-  if (!active) return;  // after the barrier: lanes of a ragged last strip store nothing
+  if (!active) return;  // after the barriers: lanes of a ragged last strip store nothing
 
-  // quantize from the registers; tile positions without a token get zeros
+  // Quantize from the registers; tile positions without a token get zeros.  Token position
+  // t -> frame t % F, tile (t / F) % TX of tile row (t / F) / TX; when the rows of a pass
+  // are a whole number of tile rows (rows % (F * TX) == 0) the offset grows by a constant per pass.
+  const uint32_t frame3 = (uint32_t)(3 * g.plane), trs = (uint32_t)g.th * (uint32_t)g.W;
+  const uint32_t lane_off = r * (uint32_t)g.W + cc;
+  uint32_t gi0, f0, ty0, tx0;
+  fd_divmod(g.dF, row, gi0, f0);
+  fd_divmod(g.dTX, gi0, ty0, tx0);
+  const uint32_t off0 = f0 * frame3 + ty0 * trs + tx0 * (uint32_t)g.tw + lane_off;
+  const uint32_t pass_step = p.pass_step;  // bytes per pass, 0 if not constant
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const uint32_t t = row + (uint32_t)i * rows;
@@ -492,16 +511,28 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
       widen_atom<DT>(v[i], x);
       o = quantize_atom(x, mnv, inv);
     }
-    stream_store<u32x2>(code_addr(g, fbase, t), o);
+    uint32_t off = off0 + (uint32_t)i * pass_step;
+    if (pass_step == 0u) {
+      uint32_t gi, f, ty, tx;
+      fd_divmod(g.dF, t, gi, f);
+      fd_divmod(g.dTX, gi, ty, tx);
+      off = f * frame3 + ty * trs + tx * (uint32_t)g.tw + lane_off;
+    }
+    stream_store<u32x2>(fplane + (size_t)off, o);
   }
-  for (uint32_t t = row + (uint32_t)NI * rows; t < (uint32_t)g.FG; t += rows)
-    stream_store<u32x2>(code_addr(g, fbase, t), u32x2{0u, 0u});
+  for (uint32_t t = row + (uint32_t)NI * rows; t < (uint32_t)g.FG; t += rows) {
+    uint32_t gi, f, ty, tx;
+    fd_divmod(g.dF, t, gi, f);
+    fd_divmod(g.dTX, gi, ty, tx);
+    stream_store<u32x2>(fplane + (size_t)(f * frame3 + ty * trs + tx * (uint32_t)g.tw + lane_off), u32x2{0u, 0u});
+  }
 }
 
 template <int DT, bool UNIFORM, bool RESIDENT>
 __global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
-  __shared__ float red_lo[kMaxWaves][kMaxStripAtoms * 8];
-  __shared__ float red_hi[kMaxWaves][kMaxStripAtoms * 8];
+  // partial column extremes of the waves; the last row carries the finished {mn} / {inv} of the strip
+  __shared__ float red_lo[kMaxWaves + 1][kMaxStripAtoms * 8];
+  __shared__ float red_hi[kMaxWaves + 1][kMaxStripAtoms * 8];
   // Workgroups go to the 8 XCDs round-robin.  Each XCD gets one contiguous range
   // of the per-channel units and one of the per-token units, so neighbouring
   // strips and token blocks share an L2 and every XCD has the same mix of work.
@@ -567,6 +598,7 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
   // per-channel part: strips of 8*strip_atoms channels
   p.n_strips = (g.apt + p.strip_atoms - 1) / p.strip_atoms;
   p.rows = threads / p.strip_atoms;
+  p.pass_step = p.rows % (g.F * g.TX) == 0 ? (uint32_t)(p.rows / (g.F * g.TX)) * (uint32_t)g.th * (uint32_t)g.W : 0u;
   const int64_t per_kind = (int64_t)p.n_chunks * 3 * g.LG;
   const int64_t units_ch = per_kind * p.n_kinds_ch * p.n_strips;
   const int64_t units_tok = per_kind * p.n_kinds_tok * p.tbc;
