@@ -201,6 +201,24 @@ __device__ __forceinline__ uint8_t* code_addr(const Geo& g, uint8_t* fbase, uint
 
 // ------------------------------------------------------------ per-token groups
 
+// min / max over the 16 lanes of a DPP row (every lane gets the result).  Each step pairs a lane
+// with one that holds a different part of the row: neighbours, the other pair of the quad, the
+// mirrored half row, the mirrored row.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ void head_minmax16(float& lo, float& hi) {
+  lo = __builtin_fminf(lo, dpp_move<0xB1>(lo));   // quad_perm [1,0,3,2]
+  hi = __builtin_fmaxf(hi, dpp_move<0xB1>(hi));
+  lo = __builtin_fminf(lo, dpp_move<0x4E>(lo));   // quad_perm [2,3,0,1]
+  hi = __builtin_fmaxf(hi, dpp_move<0x4E>(hi));
+  lo = __builtin_fminf(lo, dpp_move<0x141>(lo));  // row_half_mirror
+  hi = __builtin_fmaxf(hi, dpp_move<0x141>(hi));
+  lo = __builtin_fminf(lo, dpp_move<0x140>(lo));  // row_mirror
+  hi = __builtin_fmaxf(hi, dpp_move<0x140>(hi));
+}
+
 template <int DT, bool UNIFORM>
 __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t unit) {
   constexpr int U = KVC_PACK_U;
@@ -240,7 +258,38 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
   const bool leader = (ca & (glanes - 1u)) == 0u;
 
   const int32_t step = p.tpp;
-  for (int32_t tb0 = t0; tb0 < t1; tb0 += U * step) {
+  int32_t tb0 = t0;
+  // whole passes of U tokens that all exist: no branches between the loads and the stores
+  const int32_t full_end = n < t1 ? n : t1;
+  for (; tb0 + U * step <= full_end; tb0 += U * step) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int32_t t = tb0 + u * step + (int32_t)tsub;
+      v[u] = stream_load<u32x4>(src + (int64_t)t * p.ts);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int32_t t = tb0 + u * step + (int32_t)tsub;
+      float lo, hi;
+      atom_minmax<DT>(v[u], lo, hi);
+      if (glanes == 16u) {  // D = 128: the 16 lanes of a head are one DPP row
+        head_minmax16(lo, hi);
+      } else {
+        for (uint32_t m = 1; m < glanes; m <<= 1) {
+          lo = __builtin_fminf(lo, __shfl_xor(lo, (int)m));
+          hi = __builtin_fmaxf(hi, __shfl_xor(hi, (int)m));
+        }
+      }
+      const GroupParams q = group_params(lo, hi);
+      float x[8];
+      widen_atom<DT>(v[u], x);
+      const u32x2 o = quantize_atom(x, q.mn, q.inv);
+      stream_store<u32x2>(code_addr(g, fbase, (uint32_t)t), o);
+      if (leader) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{q.scale, q.mn};
+    }
+  }
+  for (; tb0 < t1; tb0 += U * step) {
     u32x4 v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -440,12 +489,12 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
   for (int i = 0; i < 8; ++i) mnv[i] = inv[i] = 0.f;
 
   if (n > 0) {
-    const uint32_t nm1 = (uint32_t)n - 1u;
+    // byte offsets grow by a constant per pass; rows past the last token repeat it (min / max unchanged)
+    const uint32_t last = ((uint32_t)n - 1u) * ts2 + e * 2u, off_row = row * ts2 + e * 2u, off_step = rows * ts2;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const uint32_t t = row + (uint32_t)i * rows;
-      // a repeated token leaves min / max unchanged
-      v[i] = stream_load<u32x4>(srcb + (size_t)(uint32_t)((t < nm1 ? t : nm1) * ts2 + e * 2u));
+      const uint32_t off = off_row + (uint32_t)i * off_step;
+      v[i] = stream_load<u32x4>(srcb + (size_t)(off < last ? off : last));
     }
     ColumnStats<DT> st;
     st.init();
