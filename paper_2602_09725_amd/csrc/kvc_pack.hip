@@ -8,10 +8,11 @@
 //    holds an atom of 8 consecutive elements; the D/8 lanes of a head reduce
 //    min/max with a cross-lane butterfly, so the input is read exactly once.
 //  * per-channel groups (one group = one channel over the valid tokens of a
-//    chunk): a workgroup owns a strip of channels of one (chunk, kind, layer),
-//    streams the strip once for the column min/max (registers + one LDS step
-//    across waves), then streams it again to quantize.  The strip (tokens x strip
-//    bytes) is sized so the second read is served from cache, not HBM.
+//    chunk): a workgroup owns a strip of channels of one (chunk, kind, layer).
+//    A chunk of up to 2048 tokens is loaded once into the registers of a
+//    1024-thread workgroup, reduced to the column min/max (registers + one LDS
+//    step across waves) and quantized from the registers; longer chunks stream
+//    the strip twice (statistics, then quantization).
 // Both kernels write every byte of their part of the frame section, zero for
 // tile positions without a token and for the planes of layers beyond L, so the
 // caller never has to clear the buffer.
@@ -399,20 +400,29 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
       }
     }
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float l0 = red_lo[0][a * 8 + i], h0 = red_hi[0][a * 8 + i];
+    // one thread per channel of the strip finishes the reduction and derives the group's parameters
+    float* par_mn = &red_lo[kMaxWaves][0];
+    float* par_inv = &red_hi[kMaxWaves][0];
+    if (tid < sa * 8u) {
+      float l0 = red_lo[0][tid], h0 = red_hi[0][tid];
       for (uint32_t w = 1; w < n_waves; ++w) {
-        l0 = __builtin_fminf(l0, red_lo[w][a * 8 + i]);
-        h0 = __builtin_fmaxf(h0, red_hi[w][a * 8 + i]);
+        l0 = __builtin_fminf(l0, red_lo[w][tid]);
+        h0 = __builtin_fmaxf(h0, red_hi[w][tid]);
       }
       const GroupParams q = group_params(l0, h0);
-      mnv[i] = q.mn;
-      inv[i] = q.inv;
-      if (row == 0 && active) {
-        float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + e + i);
+      par_mn[tid] = q.mn;
+      par_inv[tid] = q.inv;
+      const uint32_t ch = strip * sa * 8u + tid;
+      if (ch < (uint32_t)g.C) {
+        float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + ch);
         *reinterpret_cast<f32x2*>(mp) = f32x2{q.scale, q.mn};
       }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      mnv[i] = par_mn[a * 8 + i];
+      inv[i] = par_inv[a * 8 + i];
     }
   }
 

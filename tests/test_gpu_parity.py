@@ -78,6 +78,17 @@ def test_small_geometries(shape, modes, dtype):
     full_check(glo, olo, kv, n, dtype, block_size=bs, tag="small")
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("modes", [(0, 1), (0, 0)])
+def test_long_chunks_take_the_two_pass_strip_body(dtype, modes):
+    """Chunks longer than the 2048 tokens a register-resident strip holds (the paper's chunks are 10K tokens,
+    Sec. 4 item (1)): the per-channel kinds then stream their strip twice."""
+    L, H, D, T, n, bs = 2, 8, 128, 2560, 2560 + 333, 16
+    glo, olo = hz.layouts(L, H, D, dtype, T, 8, 128, 8, 40, *modes)
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=2560, device="cuda")
+    full_check(glo, olo, kv, n, dtype, block_size=bs, tag="long chunk")
+
+
 PAPER_RESOLUTIONS = {"240P": (426, 240), "480P": (854, 480), "640P": (1138, 640), "1080P": (1920, 1080)}
 
 
