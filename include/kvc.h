@@ -258,7 +258,9 @@ size_t kvc_meta_staging_size(const kvc_layout* layout, int32_t order);
  * staging buffer until it is full (it holds floor(frame_staging_bytes /
  * kvc_frame_size) frames, at most a chunk's), announced with one event and
  * restored with one kvc_restore_paged_frames launch per run; the pairs a run
- * needs are copied before it.
+ * needs are copied before it.  In KVC_ORDER_LAYER a buffer that holds at least
+ * 2*F frames receives the K and the V frames of a (chunk, layer group) in one
+ * two-row strided copy.
  *   d_frame_staging  HOST array of n_frame_staging (2..64) DEVICE buffers of
  *                    frame_staging_bytes >= kvc_frame_size, 256-byte aligned
  *   d_meta_staging   HOST array of n_meta_staging (2..64) DEVICE buffers of

@@ -485,6 +485,27 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
     }
   };
 
+  // K and V frames of one layer group of chunk i as one strided copy (two rows, LG * F frames apart in the
+  // blob, back to back in the slot), when both runs still fit into the slot being filled.
+  auto add_group_2d = [&](int i, int lg, int ms) -> bool {
+    if (fill_frames == per_slot) flush();
+    if (!ok || per_slot - fill_frames < 2 * (int64_t)g.F) return false;
+    const uint8_t* blob = static_cast<const uint8_t*>(chunks[i].host_blob);
+    const int fs = (int)(fill_no % n_frame_staging);
+    if (fill.empty()) {
+      fill_first_unit = unit_no;
+      if (fill_no >= n_frame_staging) ok = hipStreamWaitEvent(cs, frames_ring.freed[fs], 0) == hipSuccess;
+    }
+    const size_t off = (size_t)fill_frames * frame_size, run = (size_t)g.F * frame_size;
+    if (ok)
+      ok = hipMemcpy2DAsync(static_cast<uint8_t*>(d_frame_staging[fs]) + off, run, blob + (size_t)lg * run,
+                            (size_t)g.LG * run, run, 2, hipMemcpyHostToDevice, cs) == hipSuccess;
+    fill.push_back(Piece{i, (int64_t)lg * g.F, g.F, off, ms, lg, false});
+    fill.push_back(Piece{i, ((int64_t)g.LG + lg) * g.F, g.F, off + run, ms, lg, true});
+    fill_frames += 2 * (int64_t)g.F;
+    return true;
+  };
+
   if (ok) {
     if (t_begin) ok = hipEventRecord(t_begin, cs) == hipSuccess;
     if (order == KVC_ORDER_CHUNK) {
@@ -497,6 +518,7 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
       for (int lg = 0; lg < g.LG && ok; ++lg)
         for (int i = 0; i < n_chunks && ok; ++i) {
           const int ms = begin_unit(i, lg);
+          if (add_group_2d(i, lg, ms)) continue;
           add_run(i, (int64_t)lg * g.F, g.F, ms, lg, false);                   // K frames of the group
           add_run(i, ((int64_t)g.LG + lg) * g.F, g.F, ms, lg, true);           // V frames of the group
         }

@@ -629,30 +629,18 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
   if (p.n_kinds_tok > 0 && (glanes > 64 || (glanes & (glanes - 1)) != 0)) return KVC_ERR_UNSUPPORTED;
   // Per-channel kinds whose chunk fits the register-resident strip run with 1024
   // threads (the strip then spans 128 token rows x 16 loads = 2048 tokens).
-#ifndef KVC_PACK_RESIDENT
-#define KVC_PACK_RESIDENT 1
-#endif
-#ifndef KVC_PACK_RES_THREADS
-#define KVC_PACK_RES_THREADS 1024
-#endif
-#ifdef KVC_PACK_STRIP_ATOMS
-  p.strip_atoms = KVC_PACK_STRIP_ATOMS;
-#else
+  constexpr int kResidentThreads = 1024;
   p.strip_atoms = 8;  // 64 channels: 128-byte input rows, 64-byte code rows
-#endif
-  p.resident = KVC_PACK_RESIDENT && p.n_kinds_ch > 0 && g.T <= kResidentLoads * (KVC_PACK_RES_THREADS / p.strip_atoms) &&
+  // 32-bit byte offsets inside the chunk's input rows and frame section are part of the resident body
+  p.resident = p.n_kinds_ch > 0 && g.T <= kResidentLoads * (kResidentThreads / p.strip_atoms) &&
                        (int64_t)g.T * p.ts * 2 < (1ll << 32) && g.frame_bytes < (1ll << 32)
                    ? 1
                    : 0;
-  const int want = p.resident ? KVC_PACK_RES_THREADS : 256;
+  const int want = p.resident ? kResidentThreads : 256;
   p.tpp = g.apt >= want ? 1 : want / g.apt;
   p.dapt = make_fastdiv((uint32_t)g.apt);
-  const int threads = p.resident ? KVC_PACK_RES_THREADS : (g.apt * p.tpp + 63) / 64 * 64;
-#ifdef KVC_PACK_TB
-  p.tb = KVC_PACK_TB;
-#else
-  p.tb = 256;
-#endif
+  const int threads = p.resident ? kResidentThreads : (g.apt * p.tpp + 63) / 64 * 64;
+  p.tb = 256;  // token positions per workgroup of the per-token kinds
   p.tbc = (g.FG + p.tb - 1) / p.tb;
   // per-channel part: strips of 8*strip_atoms channels
   p.n_strips = (g.apt + p.strip_atoms - 1) / p.strip_atoms;

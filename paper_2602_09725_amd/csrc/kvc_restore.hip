@@ -255,11 +255,7 @@ __device__ __forceinline__ void restore_body_lanes(const RestoreParams& p, uint3
 // block-table entries also share an L2, and each L2 streams whole frame rows.
 template <int DT, bool PAGED, bool WAVES>
 __global__ void __launch_bounds__(1024) restore_kernel(const RestoreParams p) {
-#ifdef KVC_NO_XCD_REMAP
-  const uint32_t unit = blockIdx.x;
-#else
   const uint32_t unit = (blockIdx.x & 7u) * p.units_per_xcd + (blockIdx.x >> 3);
-#endif
   if (unit >= p.n_units) return;
   uint32_t rest, tbi, l, kind, c, ff = 0;
   const uint8_t* fsec;  // plane of layer l: frame 0 of its group (chunk call) or the one frame (frame call)
