@@ -112,6 +112,44 @@ def test_multi_resolution_versions_of_one_cache():
             assert torch.equal(out.view(torch.int16), first[2].view(torch.int16)), f"{name} restores differently from {first[0]}"
 
 
+def random_geometries(count, seed):
+    """Seeded random layouts inside the documented limits: any C = H*D up to 8192 with D a power of two, any tile
+    th*tw == C with tw a multiple of 8, any tile grid, chunk length, layer count, ragged token count and block size."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        H = int(rng.choice([1, 2, 3, 4, 5, 8, 16, 32]))
+        D = int(rng.choice([8, 16, 32, 64, 128, 256]))
+        C = H * D
+        if C > 8192:
+            continue
+        tws = [w for w in range(8, C + 1, 8) if C % w == 0]
+        tw = int(rng.choice(tws))
+        th = C // tw
+        TX, TY = int(rng.integers(1, 7)), int(rng.integers(1, 7))
+        T = int(rng.integers(1, 40 * TX * TY + 1))
+        L = int(rng.integers(1, 8))
+        n = int(rng.integers(1, 3 * T + 1))
+        F = -(-T // (TX * TY))
+        frame_bytes = 2 * ((L + 2) // 3) * F * 3 * TY * th * TX * tw * (-(-n // T))
+        if L * 2 * n * C > 4_000_000 or frame_bytes > 64 * 2**20:
+            continue
+        bs = int(rng.choice([1, 2, 7, 16, 32]))
+        modes = (int(rng.integers(0, 2)), int(rng.integers(0, 2)))
+        dtype = "f16" if rng.integers(0, 2) == 0 else "bf16"
+        out.append((L, H, D, T, th, tw, TX, TY, n, bs, modes, dtype))
+    return out
+
+
+@pytest.mark.parametrize("geo", random_geometries(24, seed=20260209), ids=lambda g: "L%d_H%d_D%d_T%d_t%dx%d_g%dx%d_n%d_b%d" % g[:10])
+def test_random_geometries(geo):
+    L, H, D, T, th, tw, TX, TY, n, bs, modes, dtype = geo
+    glo, olo = hz.layouts(L, H, D, dtype, T, th, tw, TX, TY, *modes)
+    assert hz.kvc.layout_validate(glo) == 0
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=31 * L + H + D + n, device="cuda")
+    full_check(glo, olo, kv, n, dtype, block_size=bs, tag="random")
+
+
 def adversarial_kv(L, H, D, n, dtype):
     """Values that stress the quantizer: constant groups, +-0, extremes, exact ties, subnormals, huge ranges."""
     g = torch.Generator().manual_seed(77)
