@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # (scaled by what the counters read for a plain copy of known size), keyed by a hash of the kernel
 # sources they were taken with: once the kernels change the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "6ac621261811e8ed": {"pack": 6803381657, "restore": 6513956864},
+    "2a4a1472524ee0b3": {"pack": 6803236659, "restore": 6513957888},
 }
 
 
