@@ -507,6 +507,25 @@ def test_frame_ranges_and_small_frame_pipeline(shape, dtype):
                 assert bool((m[msz:] == 0xEE).all())
 
 
+def test_restore_reads_frames_from_mapped_pinned_host_memory():
+    """The frame pointer may be pinned host memory that is mapped into the device (no staging copy at all)."""
+    L, H, D, T, n, bs = 3, 8, 128, 96, 96 + 40, 16
+    glo, olo = hz.layouts(L, H, D, "f16", T, 8, 128, 4, 8)
+    kv = kv_synth.make_kv(L, H, D, n, torch.float16, seed=12, device="cuda")
+    frames, meta = hz.gpu_pack(glo, kv, n)
+    host = torch.empty(frames.numel(), dtype=torch.uint8, pin_memory=True)
+    host.copy_(frames)
+    torch.cuda.synchronize()
+    n_logical = (n + bs - 1) // bs
+    tab = kv_synth.make_block_table(n_logical, n_logical + 2, 5).cuda()
+    ref = hz.PagedCache(L, n_logical + 2, bs, H * D)
+    hz.gpu_restore_paged(glo, frames, meta, 0, n, ref, tab)
+    got = hz.PagedCache(L, n_logical + 2, bs, H * D)
+    hz.gpu_restore_paged(glo, host, meta, 0, n, got, tab)
+    for l in range(L):
+        assert torch.equal(got.layers[l], ref.layers[l])
+
+
 def test_frame_restore_bad_block_ids():
     L, H, D, T, n, bs = 3, 8, 128, 64, 64, 16
     glo, olo = hz.layouts(L, H, D, "f16", T, 8, 128, 4, 4)
