@@ -134,7 +134,7 @@ def main():
         gbps = nbytes / (avg_ms * 1e-3) / 1e9
         return {"kernel": name, "bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": traffic.get(name.split("_")[0]),
-                "avg_ms": round(avg_ms, 4),
+                "avg_ms": round(avg_ms, 4), "median_ms": round(statistics.median(all_ms), 4),
                 "min_ms": round(min(all_ms), 4), "algorithmic_bytes": nbytes}
 
     roof_pack = roof("pack_kernel (kvc_pack)", pack_bytes, pack_avg, pack_ms)
