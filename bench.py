@@ -155,6 +155,20 @@ def main():
     copy_gbps = 2 * a.numel() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del a, b
 
+    # the same restore with physical blocks in logical order: what the seeded random placement of the workload costs
+    seq_table = torch.arange(n_logical, dtype=torch.int32, device=dev)
+    seq_ms = []
+    for it in range(8):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        kvc.kvc_restore_paged(lo, frames.data_ptr(), meta.data_ptr(), 0, w.n_tokens, ptrs.data_ptr(), n_logical, bs,
+                              seq_table.data_ptr(), n_logical, err.data_ptr(), sh)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        if it >= 2:
+            seq_ms.append(e0.elapsed_time(e1))
+    seq_avg = sum(seq_ms) / len(seq_ms)
+
     out = {
         "metric": "KV restore/pack GB/s at 1 MI355X + % of HBM peak; 32K-token fetch-to-ready ms",
         "value": round((pack_bytes + restore_bytes) / (ms_per_step * 1e-3) / 1e9, 1),
@@ -169,6 +183,9 @@ def main():
         "roofline": dominant,
         "roofline_other_kernel": other,
         "pct_of_hbm_peak": {"restore": round(100 * roof_rest["frac"], 2), "pack": round(100 * roof_pack["frac"], 2)},
+        "restore_sequential_blocks": {"avg_ms": round(seq_avg, 4),
+                                      "achieved": round(restore_bytes / (seq_avg * 1e-3) / 1e9, 1),
+                                      "frac": round(restore_bytes / (seq_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "device_copy_GBps": round(copy_gbps, 1),
     }
 
