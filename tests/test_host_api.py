@@ -235,3 +235,22 @@ def test_layout_set_resolution(kvc_lib):
     lo = good()
     assert kvc.layout_set_resolution(lo, 100, 4) == 0 and (lo.tiles_x, lo.tiles_y) == (1, 1)   # smaller than a tile
     assert kvc.layout_set_resolution(lo, 0, 240) == 1 and kvc.layout_set_resolution(lo, 426, -1) == 1
+
+
+def test_bench_contract_pieces_that_need_no_gpu():
+    """bench.py: algorithmic bytes of the benchmark workload (1 code byte + 2 output bytes + pairs per element for
+    restore; 2 input bytes + every frame byte + pairs for pack) and the refusal of more than one GPU."""
+    import subprocess
+    import sys
+
+    import bench
+    import kv_synth
+    w = kv_synth.WORKLOADS["llama3_8b_32k_paged"]
+    fb, mb, _ = kvc.chunk_sizes(good())
+    elems, pack_bytes, restore_bytes = bench.algorithmic_bytes(w, fb, mb)
+    assert elems == 32 * 2 * 32768 * 1024
+    pairs = 16 * (32 * 1024 + 32 * 2048 * 8) * 8              # per chunk: K per channel, V per (token, head)
+    assert restore_bytes == 3 * elems + pairs == 6_513_754_112
+    assert pack_bytes == 2 * elems + 16 * fb + pairs == 6_580_862_976
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
