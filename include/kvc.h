@@ -279,7 +279,11 @@ size_t kvc_meta_staging_size(const kvc_layout* layout, int32_t order);
  *                    enqueued to each group being ready.
  *   fetch_to_ready_ms HOST out or NULL.  The call blocks until the last restore
  *                    has finished if either time output is non-NULL; otherwise it
- *                    returns after enqueueing.
+ *                    returns after enqueueing.  In that form it enqueues copies,
+ *                    kernels and event edges only, so it may be recorded into a
+ *                    HIP graph by stream capture (begin the capture on
+ *                    copy_stream and make it wait for compute_stream before the
+ *                    capture ends) and replayed.
  * Other arguments, blob format and error behaviour as kvc_fetch_pipeline. */
 kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_chunk* chunks, int32_t n_chunks,
                                      void* const* d_frame_staging, size_t frame_staging_bytes, int32_t n_frame_staging,

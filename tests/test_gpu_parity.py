@@ -612,3 +612,25 @@ def test_config_frame_pipeline_matches_chunk_restore():
             assert torch.equal(cache.layers[l], ref.layers[l]), f"group {g} event fired before layer {l} was complete"
     s_comp.synchronize()
     torch.cuda.synchronize()
+    # the non-blocking form can be captured into a HIP graph (it holds copies, kernels and event edges only, no
+    # memset): every replay, with eager work between the replays, gives the cache of the eager call
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s_copy):
+        kvc.kvc_fetch_pipeline_frames(glo, [(b.data_ptr(), blob_bytes, T) for b in blobs],
+                                      [s.data_ptr() for s in fstage], per_slot * fs, [s.data_ptr() for s in mstage], msz,
+                                      cache.ptrs.data_ptr(), n_logical, bs, table.data_ptr(), n_logical,
+                                      cache.err.data_ptr(), s_copy.cuda_stream, s_comp.cuda_stream,
+                                      order=kvc.KVC_ORDER_LAYER, timed=False)
+        joined = torch.cuda.Event()
+        joined.record(s_comp)
+        s_copy.wait_event(joined)   # the capture ends on the stream it began on
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in cache.layers:
+            t.fill_(hz.POISON)      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(cache.err.item()) == 0
+        for l in range(w.L):
+            assert torch.equal(cache.layers[l], ref.layers[l]), f"graph replay {rep}: layer {l}"
