@@ -13,14 +13,18 @@
  *                                tensors in groups of F; the F tensors of a group
  *                                at one position in F consecutive frames; three
  *                                layers -> three independently coded planes
- *   Sec. 3.2.2 rules i-iii       tile = row-major reshape of the H*D vector,
- *                                heads and in-head order kept (tiles (8,512),
- *                                (8,128), (16,64) in the closing paragraph)
+ *   Sec. 3.2.2 rules i-iii       tile = geometric tiling of the H*D vector, heads
+ *                                and in-head order kept: head_num reshaped to
+ *                                (h1, h2), head_dim to (d1, d2), tile = (h1*d1,
+ *                                h2*d2) (the closing paragraph's (32,128) ->
+ *                                (8,4) x (1,128) -> (8,512); tiles (8,512),
+ *                                (8,128), (16,64) found there)
  *   Sec. 4 item (1)              tensors become integers before encoding; chunking
  *   Sec. 3.3.2 restoration       frame -> KV tensor -> preallocated paged slots
  *
  * Pins (tests marked "not gpu"): index map against the paper's three worked
- * tiles and rules i-iii, the temporal-alignment and three-plane statements,
+ * tiles and rules i-iii, the two-level tilings against numpy's own
+ * reshape / transpose / reshape, the temporal-alignment and three-plane statements,
  * brute-force bijection, a layout special case equal to a numpy reshape, the
  * uniform-quantizer error bound, exact extremes, numpy's own float16 rounding,
  * paged placement against a poison-filled cache, the frame-wise restore against
@@ -42,9 +46,12 @@ typedef struct {
   int32_t TX, TY;       /* tile grid of one frame                         */
   int32_t k_mode;       /* 0 = one group per channel per chunk            */
   int32_t v_mode;       /* 1 = one group per (token, head)                */
+  int32_t seg;          /* d2: consecutive elements of one head per tile row;
+                           0 = the row-major retile, min(D, tw)             */
 } kvco_layout;
 
 int kvco_check(const kvco_layout* lo);                       /* 0 if consistent */
+int64_t kvco_segment(const kvco_layout* lo);                 /* d2 (resolves seg = 0) */
 int64_t kvco_frames_per_group(const kvco_layout* lo);        /* F  */
 int64_t kvco_frame_bytes(const kvco_layout* lo);             /* per chunk */
 int64_t kvco_meta_floats(const kvco_layout* lo);             /* per chunk, in floats */
@@ -82,4 +89,5 @@ int kvco_restore_paged_frame(const kvco_layout* lo, const uint8_t* frame, const 
                              int64_t first_token, int64_t n_tokens, uint16_t* const* layer_cache, int64_t num_blocks,
                              int32_t block_size, const int32_t* block_table, int64_t table_len, uint32_t* err);
 int kvco_threads(void); /* threads the chunk/layer loops run on */
+const char* kvco_build_id(void); /* hash of the sources and flags this binary was built from */
 #endif

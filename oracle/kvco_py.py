@@ -15,14 +15,13 @@ _lib = None
 
 
 class Layout(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("L", "H", "D", "dtype", "T", "th", "tw", "TX", "TY", "k_mode", "v_mode")]
+    _fields_ = [(n, C.c_int32) for n in ("L", "H", "D", "dtype", "T", "th", "tw", "TX", "TY", "k_mode", "v_mode", "seg")]
 
 
 def lib():
     global _lib
     if _lib is None:
-        path = build_oracle.LIB if os.path.exists(build_oracle.LIB) else build_oracle.build()
-        _lib = C.CDLL(path)
+        _lib = C.CDLL(build_oracle.ensure_current())  # rebuilt when stale: see build_oracle
         i64, p = C.c_int64, C.c_void_p
         LP = C.POINTER(Layout)
         _lib.kvco_check.argtypes = [LP]
@@ -53,8 +52,9 @@ def lib():
     return _lib
 
 
-def make_layout(L, H, D, dtype, T, th, tw, TX, TY, k_mode=0, v_mode=1):
-    return Layout(L, H, D, dtype, T, th, tw, TX, TY, k_mode, v_mode)
+def make_layout(L, H, D, dtype, T, th, tw, TX, TY, k_mode=0, v_mode=1, seg=0):
+    """seg = d2 of the two-level tiling of Sec. 3.2.2 (0: the row-major retile)."""
+    return Layout(L, H, D, dtype, T, th, tw, TX, TY, k_mode, v_mode, seg)
 
 
 def frames_per_group(lo):

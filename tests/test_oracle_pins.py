@@ -112,6 +112,38 @@ def test_tile_is_row_major_reshape(oracle, H, D, th, tw):
             assert tile[r, c] == h * D + d
 
 
+@pytest.mark.parametrize("H,D,h1,d1", [(32, 128, 8, 1), (32, 128, 8, 4), (8, 128, 4, 2), (8, 128, 8, 2), (8, 128, 1, 16),
+                                       (4, 16, 2, 2), (4, 16, 1, 1), (4, 16, 4, 16)])
+def test_two_level_tile_is_numpy_reshape_transpose_reshape(oracle, H, D, h1, d1):
+    """Sec. 3.2.2: head_num -> (h1, h2), head_dim -> (d1, d2), tile (h1*d1, h2*d2) -- e.g. (32,128) -> (8,4) x
+    (1,128) -> (8,512).  As numpy states it: the [h1][h2][d1][d2] view of the token's [H][D] matrix with the two
+    middle axes exchanged, flattened to two axes.  No element leaves its head (rule i), runs of d2 elements keep their
+    order (rule ii), heads keep theirs (rule iii)."""
+    h2, d2 = H // h1, D // d1
+    th, tw = h1 * d1, h2 * d2
+    lo = oracle.make_layout(L=1, H=H, D=D, dtype=F16, T=1, th=th, tw=tw, TX=1, TY=1, seg=d2)
+    assert oracle.lib().kvco_check(lo) == 0
+    tile = np.arange(H * D).reshape(h1, h2, d1, d2).transpose(0, 2, 1, 3).reshape(th, tw)
+    for h in range(H):
+        for d in range(D):
+            r, c = divmod(oracle.frame_offset(lo, 0, 0, 0, h, d), tw)
+            assert tile[r, c] == h * D + d, (h, d)
+    if d1 == 1 or h2 == 1:   # these members of the family are the plain row-major retile: seg = 0 means the same
+        lo0 = oracle.make_layout(L=1, H=H, D=D, dtype=F16, T=1, th=th, tw=tw, TX=1, TY=1)
+        assert all(oracle.frame_offset(lo0, 0, 0, 0, h, d) == oracle.frame_offset(lo, 0, 0, 0, h, d)
+                   for h in range(H) for d in range(0, D, 3))
+
+
+def test_two_level_tile_rejects_inconsistent_segments(oracle):
+    ok = dict(L=1, H=8, D=128, dtype=F16, T=1, TX=1, TY=1)
+    check = oracle.lib().kvco_check
+    assert check(oracle.make_layout(th=8, tw=128, seg=64, **ok)) == 0    # heads (4,2), dims (2,64)
+    assert check(oracle.make_layout(th=16, tw=64, seg=16, **ok)) == 0    # heads (2,4), dims (8,16)
+    assert check(oracle.make_layout(th=8, tw=128, seg=48, **ok)) != 0    # 48 divides neither 128
+    assert check(oracle.make_layout(th=8, tw=128, seg=256, **ok)) != 0   # longer than a head
+    assert check(oracle.make_layout(th=1, tw=1024, seg=64, **ok)) != 0   # a row would need 16 heads, there are 8
+
+
 def test_rules_order_preserving(oracle):
     """Rules i-iii: raster order of a token's bytes == (head, dim) order."""
     lo = oracle.make_layout(L=1, H=8, D=32, dtype=F16, T=1, th=16, tw=16, TX=1, TY=1)
@@ -169,7 +201,8 @@ def test_three_layers_three_planes(oracle):
 
 
 @pytest.mark.parametrize("kw", [dict(), dict(L=3, T=7, TX=1, TY=2), dict(L=1, H=1, D=8, th=1, tw=8, T=5, TX=2, TY=2),
-                                dict(L=5, th=32, tw=1, T=6, TX=3, TY=1)])
+                                dict(L=5, th=32, tw=1, T=6, TX=3, TY=1),
+                                dict(L=2, H=4, D=16, th=4, tw=16, seg=8, T=5, TX=2, TY=2)])
 def test_bijection_brute_force(oracle, kw):
     """Every valid element has its own byte inside the chunk section; count = 2*L*T*C."""
     lo = small_layout(oracle, **kw)
