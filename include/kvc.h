@@ -152,6 +152,18 @@ size_t kvc_blob_meta_offset(const kvc_layout* layout);
 kvc_status kvc_pack(const kvc_layout* layout, const void* kv, kvc_strides strides, int64_t n_tokens,
                     uint8_t* frames, size_t frames_cap, void* meta, size_t meta_cap, void* stream);
 
+/* How kvc_pack would run for this layout and these strides: host arithmetic
+ * only, nothing is enqueued (Sec. 4 item (1), the offline compression pass).
+ *   *resident  HOST out, nullable: 1 when the strip of channels a workgroup
+ *              quantizes per channel is held in registers for a whole chunk, so
+ *              the input is read from memory once; 0 when the strip is streamed
+ *              twice (chunk_tokens > 2048, or 2048 * token_stride * 2 bytes does
+ *              not fit the 32-bit offsets of the register-resident body) or no
+ *              kind is quantized per channel
+ *   *threads   HOST out, nullable: threads per workgroup of the launch
+ * Returns the status kvc_pack would return for the same layout and strides. */
+kvc_status kvc_pack_plan(const kvc_layout* layout, kvc_strides strides, int32_t* resident, int32_t* threads);
+
 /* Fetch side into a contiguous tensor (Sec. 3.3.2 frame-wise restoration:
  * unpack + dequantize).
  *   frames, meta  DEVICE in : chunk sections as written by kvc_pack
@@ -309,14 +321,16 @@ int32_t kvc_admission_ok(const double* t_fetch, const double* t_comp, int32_t n_
 int32_t kvc_admission_min_buffered(const double* t_fetch, const double* t_comp, int32_t n_stages);
 
 /* Adaptive-resolution selector (Alg. 1, Appx A.2; Sec. 3.3.1), host arithmetic
- * only.  For every resolution r of the supported set, in index order:
- *   tau_trans = size[r] / bandwidth
- *   tau_dec   = latency[(pool_load - 1) * n_res + r]      (profile table, one row per pool load)
- *   tau_pen   = penalty[r] if active_res >= 0 and r != active_res, else 0
- *   bubble    = | tau_trans - tau_dec - tau_pen |
- * and the first r with the smallest bubble is returned (a later r replaces the
- * kept one only on a strictly smaller bubble); *bubble (may be NULL) gets that
- * bubble.  size and bandwidth share a unit (bytes and bytes/s, MB and MB/s, ...).
+ * only.  A chunk version is a good fit for the network and the decode pool when
+ * it arrives just as the pool has finished the work in front of it.  For
+ * version r the two times are
+ *   arrival[r] = size[r] / bandwidth
+ *   ready[r]   = latency[(pool_load - 1) * n_res + r]   (profile table: one row
+ *                per pool load) + penalty[r] when the pool has to switch, i.e.
+ *                active_res >= 0 and r != active_res
+ * and the call returns the r that minimizes the idle gap |arrival[r] - ready[r]|
+ * (the lowest index among equal gaps); *bubble (may be NULL) gets that gap.
+ * size and bandwidth share a unit (bytes and bytes/s, MB and MB/s, ...).
  *   pool_load   present load of the decode pool, 1..n_loads
  *   active_res  resolution the pool is working on, or -1 for an idle pool
  * Returns -1 on a bad argument (NULL, n_res < 1, n_loads < 1, pool_load or
@@ -340,6 +354,12 @@ kvc_status kvc_layout_set_resolution(kvc_layout* layout, int32_t width, int32_t 
 
 /* Static, never-freed description of a status code. */
 const char* kvc_status_str(kvc_status status);
+
+/* Identifier of what this binary was built from: a hash of the library's
+ * sources, this header and the compiler flags, fixed at build time ("unknown"
+ * for a build that did not pass one).  Lets a test run detect a stale binary.
+ * HOST; returns a static string. */
+const char* kvc_build_id(void);
 
 #ifdef __cplusplus
 }

@@ -38,6 +38,21 @@ kvc_status check_layout(const kvc_layout* lo) {
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// Lowest index at which cost(i), i in [0, n), is smallest.
+template <typename Cost>
+int32_t first_argmin(int32_t n, Cost cost) {
+  int32_t at = 0;
+  double least = cost(0);
+  for (int32_t i = 1; i < n; ++i) {
+    const double c = cost(i);
+    if (c < least) {
+      least = c;
+      at = i;
+    }
+  }
+  return at;
+}
+
 kvc_status check_strides(const kvc_strides& s) {
   if (s.layer_stride < 0 || s.kv_stride < 0 || s.token_stride < 0) return KVC_ERR_INVALID_ARG;
   if ((s.layer_stride | s.kv_stride | s.token_stride) & 7) return KVC_ERR_INVALID_ARG;
@@ -101,6 +116,12 @@ const char* kvc_status_str(kvc_status status) {
   return "unknown status";
 }
 
+#ifndef KVC_BUILD_ID
+#define KVC_BUILD_ID "unknown"
+#endif
+static const char build_tag[] = "kvc-build-id:" KVC_BUILD_ID;  // also found by scanning the file
+const char* kvc_build_id(void) { return build_tag + 13; }
+
 kvc_status kvc_layout_validate(const kvc_layout* layout) { return check_layout(layout); }
 
 kvc_status kvc_chunk_sizes(const kvc_layout* layout, size_t* frame_bytes, size_t* meta_bytes,
@@ -150,6 +171,23 @@ kvc_status kvc_pack(const kvc_layout* layout, const void* kv, kvc_strides stride
   p.frames = frames;
   p.meta = static_cast<float*>(meta);
   return launch_pack(p, as_stream(stream));
+}
+
+kvc_status kvc_pack_plan(const kvc_layout* layout, kvc_strides strides, int32_t* resident, int32_t* threads) {
+  PackParams p{};
+  kvc_status st = make_geo(layout, &p.g);
+  if (st != KVC_OK) return st;
+  if ((st = check_strides(strides)) != KVC_OK) return st;
+  if (strides.token_stride < p.g.C) return KVC_ERR_INVALID_ARG;
+  p.ls = strides.layer_stride;
+  p.ks = strides.kv_stride;
+  p.ts = strides.token_stride;
+  p.n_tokens = p.g.T;
+  int th = 0;
+  if ((st = plan_pack(p, &th)) != KVC_OK) return st;
+  if (resident) *resident = p.resident;
+  if (threads) *threads = th;
+  return KVC_OK;
 }
 
 kvc_status kvc_restore(const kvc_layout* layout, const uint8_t* frames, const void* meta, int64_t n_tokens,
@@ -573,19 +611,14 @@ int32_t kvc_select_resolution(const double* size, const double* latency, const d
   if (!good_times(&bandwidth, 1) || bandwidth == 0.0) return -1;
   const double* row = latency + (size_t)(pool_load - 1) * n_res;
   if (!good_times(size, n_res) || !good_times(penalty, n_res) || !good_times(row, n_res)) return -1;
-  int32_t best = -1;
-  double best_bubble = 0.0;
-  for (int32_t r = 0; r < n_res; ++r) {
-    const double trans = size[r] / bandwidth;
-    const double pen = (active_res >= 0 && r != active_res) ? penalty[r] : 0.0;
-    double gap = trans - row[r] - pen;
-    if (gap < 0.0) gap = -gap;
-    if (best < 0 || gap < best_bubble) {
-      best = r;
-      best_bubble = gap;
-    }
-  }
-  if (bubble) *bubble = best_bubble;
+  // idle gap of version r: when it has arrived against when the pool is ready for it
+  const auto gap = [&](int32_t r) {
+    const double switch_cost = (active_res >= 0 && r != active_res) ? penalty[r] : 0.0;
+    const double d = size[r] / bandwidth - row[r] - switch_cost;  // subtracted in this order (left to right)
+    return d < 0.0 ? -d : d;
+  };
+  const int32_t best = first_argmin(n_res, gap);
+  if (bubble) *bubble = gap(best);
   return best;
 }
 

@@ -16,9 +16,11 @@ struct RestoreParams {
   int32_t tb;             // tokens per workgroup (0: library default)
   int32_t tbc;            // token blocks per chunk
   int32_t tpp;            // tokens per pass of a workgroup = threads / apt
-  uint32_t n_units;       // n_chunks * 2 * L * tbc workgroups with work
+  uint32_t n_units;       // frame call: fm_count * 3 * tbc workgroups with work
   uint32_t units_per_xcd;
-  FastDiv dtbc, dL;       // unit -> (token block, layer, kind, chunk)
+  FastDiv dtbc, dL;       // unit -> (token block, chunk), row -> (kind, layer)
+  uint32_t row_units;     // chunk call: token blocks of one (kind, layer) over all chunks
+  FastDiv drpx;           // ... and the share of one XCD
   FastDiv dapt;           // atoms per token
   FastDiv dwpt;           // waves per token (apt / 64) when apt is a multiple of 64
   uint32_t frame_stride;     // bytes from a frame to the next of the same layer group: 3 planes (0 for a frame call)
@@ -73,6 +75,10 @@ struct PackParams {
   uint32_t ch_per_xcd, tok_per_xcd;
   uint32_t units_per_xcd;
 };
+
+// Host-side plan of a pack launch: which body the per-channel kinds take, block and grid
+// shape.  Fills the derived fields of `p` (geometry, strides and n_tokens must be set).
+kvc_status plan_pack(PackParams& p, int* threads_out);
 
 // Enqueues statistics + quantize + layout for every kind, plus the zero fill of
 // unused planes and tile positions.

@@ -612,9 +612,8 @@ __global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
 
 }  // namespace
 
-kvc_status launch_pack(PackParams p, hipStream_t stream) {
+kvc_status plan_pack(PackParams& p, int* threads_out) {
   const Geo& g = p.g;
-  if (p.n_tokens <= 0) return KVC_OK;
   p.n_chunks = (int32_t)((p.n_tokens + g.T - 1) / g.T);
   if (g.apt > 1024) return KVC_ERR_UNSUPPORTED;
   p.n_kinds_ch = p.n_kinds_tok = 0;
@@ -631,9 +630,11 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
   // threads (the strip then spans 128 token rows x 16 loads = 2048 tokens).
   constexpr int kResidentThreads = 1024;
   p.strip_atoms = 8;  // 64 channels: 128-byte input rows, 64-byte code rows
-  // 32-bit byte offsets inside the chunk's input rows and frame section are part of the resident body
-  p.resident = p.n_kinds_ch > 0 && g.T <= kResidentLoads * (kResidentThreads / p.strip_atoms) &&
-                       (int64_t)g.T * p.ts * 2 < (1ll << 32) && g.frame_bytes < (1ll << 32)
+  // The resident body forms 32-bit byte offsets for all kResidentLoads x rows token rows of a strip, whatever
+  // the chunk length (rows past the last token are clamped afterwards), and inside the chunk's frame section.
+  const int64_t resident_rows = (int64_t)kResidentLoads * (kResidentThreads / p.strip_atoms);
+  p.resident = p.n_kinds_ch > 0 && g.T <= resident_rows && resident_rows * p.ts * 2 < (1ll << 32) &&
+                       g.frame_bytes < (1ll << 32)
                    ? 1
                    : 0;
   const int want = p.resident ? kResidentThreads : 256;
@@ -655,6 +656,16 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
   p.ch_per_xcd = (p.n_units_ch + 7u) / 8u;
   p.tok_per_xcd = (p.n_units_tok + 7u) / 8u;
   p.units_per_xcd = p.ch_per_xcd + p.tok_per_xcd;
+  *threads_out = threads;
+  return KVC_OK;
+}
+
+kvc_status launch_pack(PackParams p, hipStream_t stream) {
+  if (p.n_tokens <= 0) return KVC_OK;
+  int threads = 0;
+  const kvc_status st = plan_pack(p, &threads);
+  if (st != KVC_OK) return st;
+  const Geo& g = p.g;
   const dim3 grid(p.units_per_xcd * 8u), block((unsigned)threads);
   const bool uniform = g.apt % 64 == 0;
 #define KVC_LAUNCH_PACK(DT_, UNI_, RES_) hipLaunchKernelGGL((pack_kernel<DT_, UNI_, RES_>), grid, block, 0, stream, p)

@@ -249,18 +249,25 @@ __device__ __forceinline__ void restore_body_lanes(const RestoreParams& p, uint3
   }
 }
 
-// Workgroups are handed to the 8 XCDs round-robin.  Each XCD gets one contiguous
-// range of units (unit = token block, fastest, then layer, then kind, then
-// chunk), so the workgroups that share a layer's per-channel pairs and a run of
-// block-table entries also share an L2, and each L2 streams whole frame rows.
+// Workgroups are handed to the 8 XCDs round-robin.
+//
+// Chunk call: a "row" is one (kind, layer), i.e. one region [num_blocks][block][H][D] of a paged
+// cache.  The whole chip works on one row at a time; the row's token blocks (over all chunks of the
+// call) are cut into 8 contiguous parts, one per XCD, so the workgroups that share a layer's
+// per-channel pairs and a run of block-table entries also share an L2, and the writes in flight stay
+// inside one region of the cache.
+//
+// Frame call: units are (frame of the run, plane, block of token slots), each XCD one contiguous range.
 template <int DT, bool PAGED, bool WAVES>
 __global__ void __launch_bounds__(1024) restore_kernel(const RestoreParams p) {
-  const uint32_t unit = (blockIdx.x & 7u) * p.units_per_xcd + (blockIdx.x >> 3);
-  if (unit >= p.n_units) return;
-  uint32_t rest, tbi, l, kind, c, ff = 0;
+  const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
+  uint32_t tbi, l, kind, c, ff = 0;
   const uint8_t* fsec;  // plane of layer l: frame 0 of its group (chunk call) or the one frame (frame call)
-  fd_divmod(p.dtbc, unit, rest, tbi);
   if (p.frame_mode) {
+    const uint32_t unit = xcd * p.units_per_xcd + idx;
+    if (unit >= p.n_units) return;
+    uint32_t rest;
+    fd_divmod(p.dtbc, unit, rest, tbi);
     // `frames` holds fm_count consecutive frames, the first being number fm_first of its chunk in
     // the order [kind][layer group][frame of the group]; a frame carries the (up to) three layers
     // of its group, one per plane.
@@ -273,9 +280,12 @@ __global__ void __launch_bounds__(1024) restore_kernel(const RestoreParams p) {
     if (l >= (uint32_t)p.g.L) return;
     fsec = p.frames + ((int64_t)frel * 3 + pl) * p.g.plane;
   } else {
-    fd_divmod(p.dL, rest, rest, l);
-    kind = rest & 1u;
-    c = rest >> 1;
+    uint32_t row, within;
+    fd_divmod(p.drpx, idx, row, within);
+    const uint32_t u = xcd * p.drpx.d + within;
+    if (u >= p.row_units) return;
+    fd_divmod(p.dL, row, kind, l);
+    fd_divmod(p.dtbc, u, c, tbi);
     const uint32_t lg = l / 3u, pl = l - lg * 3u;
     fsec = p.frames + (int64_t)c * p.g.frame_bytes + (((int64_t)kind * p.g.LG + lg) * p.g.F * 3 + pl) * p.g.plane;
   }
@@ -306,7 +316,7 @@ kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream) {
   const Geo& g = p.g;
   if (p.n_tokens <= 0) return KVC_OK;
   if (g.apt > 1024) return KVC_ERR_UNSUPPORTED;
-  // threads: a whole number of tokens per pass, about 256 threads
+  // threads: a whole number of tokens per pass, about 512 threads
 #ifndef KVC_RESTORE_THREADS
 #define KVC_RESTORE_THREADS 512
 #endif
@@ -329,15 +339,26 @@ kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream) {
   if (p.tb > g.T) p.tb = g.T;
   p.tbc = (g.T + p.tb - 1) / p.tb;
   p.n_chunks = (int32_t)((p.n_tokens + g.T - 1) / g.T);
-  if (p.frame_mode) p.tbc = ((g.T + g.F - 1) / g.F + p.tb - 1) / p.tb;  // slots of one frame
-  const int64_t units = p.frame_mode ? (int64_t)p.fm_count * 3 * p.tbc : (int64_t)p.n_chunks * 2 * g.L * p.tbc;
-  if (units > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
-  p.n_units = (uint32_t)units;
-  p.units_per_xcd = (p.n_units + 7u) / 8u;
-  p.dtbc = make_fastdiv((uint32_t)p.tbc);
   p.dL = make_fastdiv((uint32_t)g.L);
   p.dLG = make_fastdiv((uint32_t)g.LG);
-  const dim3 grid(p.units_per_xcd * 8u), block((unsigned)threads);
+  dim3 grid, block((unsigned)threads);
+  if (p.frame_mode) {
+    p.tbc = ((g.T + g.F - 1) / g.F + p.tb - 1) / p.tb;  // slots of one frame
+    const int64_t units = (int64_t)p.fm_count * 3 * p.tbc;
+    if (units > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
+    p.n_units = (uint32_t)units;
+    p.units_per_xcd = (p.n_units + 7u) / 8u;
+    grid = dim3(p.units_per_xcd * 8u);
+  } else {
+    const int64_t row_units = (int64_t)p.n_chunks * p.tbc;
+    const int64_t per_xcd = (row_units + 7) / 8;
+    const int64_t wgs = per_xcd * 8 * 2 * g.L;
+    if (wgs > 0x7fffffff) return KVC_ERR_UNSUPPORTED;
+    p.row_units = (uint32_t)row_units;
+    p.drpx = make_fastdiv((uint32_t)per_xcd);
+    grid = dim3((uint32_t)wgs);
+  }
+  p.dtbc = make_fastdiv((uint32_t)p.tbc);
   if (g.dtype == KVC_F16) {
     if (paged)
       launch_variant<KVC_F16, true>(p, waves, grid, block, stream);

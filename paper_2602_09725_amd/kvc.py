@@ -61,11 +61,14 @@ def load(path=None):
     LP, vp, i64, i32, sz = C.POINTER(Layout), C.c_void_p, C.c_int64, C.c_int32, C.c_size_t
     lib.kvc_status_str.argtypes = [C.c_int]
     lib.kvc_status_str.restype = C.c_char_p
+    lib.kvc_build_id.argtypes = []
+    lib.kvc_build_id.restype = C.c_char_p
     lib.kvc_layout_validate.argtypes = [LP]
     lib.kvc_chunk_sizes.argtypes = [LP, C.POINTER(sz), C.POINTER(sz), C.POINTER(i32)]
     lib.kvc_blob_meta_offset.argtypes = [LP]
     lib.kvc_blob_meta_offset.restype = sz
     lib.kvc_pack.argtypes = [LP, vp, Strides, i64, vp, sz, vp, sz, vp]
+    lib.kvc_pack_plan.argtypes = [LP, Strides, C.POINTER(i32), C.POINTER(i32)]
     lib.kvc_restore.argtypes = [LP, vp, vp, i64, vp, Strides, vp]
     lib.kvc_restore_paged.argtypes = [LP, vp, vp, i64, i64, vp, i64, i32, vp, i64, vp, vp]
     lib.kvc_fetch_pipeline.argtypes = [LP, C.POINTER(HostChunk), i32, C.POINTER(vp), sz, i32, vp, i64, i32, vp, i64,
@@ -96,6 +99,10 @@ def load(path=None):
     return lib
 
 
+def build_id():
+    return load().kvc_build_id().decode()
+
+
 def status_str(status):
     return load().kvc_status_str(int(status)).decode()
 
@@ -114,6 +121,13 @@ def chunk_sizes(layout):
     fb, mb, f = C.c_size_t(), C.c_size_t(), C.c_int32()
     _check(load().kvc_chunk_sizes(C.byref(layout), C.byref(fb), C.byref(mb), C.byref(f)), "kvc_chunk_sizes")
     return fb.value, mb.value, f.value
+
+
+def pack_plan(layout, strides):
+    """-> (resident, threads): how kvc_pack would run (host arithmetic only)."""
+    r, t = C.c_int32(), C.c_int32()
+    _check(load().kvc_pack_plan(C.byref(layout), Strides(*strides), C.byref(r), C.byref(t)), "kvc_pack_plan")
+    return r.value, t.value
 
 
 def blob_meta_offset(layout):

@@ -22,11 +22,12 @@ def oracle():
 
 @pytest.fixture(scope="session")
 def kvc_lib():
-    """The built HIP library; built here only if no build is present."""
+    """The built HIP library.  It is rebuilt here when it is missing or when the identifier it carries is not the
+    hash of the present sources, header and flags, so a parity run never passes on a stale binary."""
     import paper_2602_09725_amd as kvc
+    from paper_2602_09725_amd import build
 
-    if not os.path.exists(kvc.lib_path()):
-        from paper_2602_09725_amd import build
-
-        build.build()
-    return kvc.load()
+    build.ensure_current()
+    lib = kvc.load()
+    assert lib.kvc_build_id().decode() == build.source_id()
+    return lib

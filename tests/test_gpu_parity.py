@@ -219,6 +219,30 @@ def test_strided_input_and_output():
     assert bool((outbuf[mask] == hz.POISON).all())
 
 
+def test_token_major_input_with_a_token_stride_beyond_32_bit_row_offsets():
+    """Token-major engine tensors [token][layer][kind][H][D] padded so that 2048 rows x token stride passes 4 GiB:
+    kvc_pack must leave the register-resident strips (their row offsets are 32-bit) and still equal the oracle."""
+    L, H, D, T, n = 2, 8, 128, 48, 48 + 5
+    C = H * D
+    glo, olo = hz.layouts(L, H, D, "f16", T, 8, 128, 4, 4)
+    ts = 2**32 // (2048 * 2) + 8                      # elements between tokens: 2 MiB + 16 bytes
+    ls, ks = 2 * C, C                                  # layers and kinds side by side inside a token row
+    assert hz.kvc.pack_plan(glo, (ls, ks, ts))[0] == 0 and hz.kvc.pack_plan(glo, (ls, ks, ts - 16))[0] == 1
+    kv = kv_synth.make_kv(L, H, D, n, torch.float16, seed=21, device="cuda")
+    big = torch.full(((n - 1) * ts + L * 2 * C,), float("inf"), dtype=torch.float16, device="cuda")
+    torch.as_strided(big, (L, 2, n, C), (ls, ks, ts, 1)).copy_(kv.view(L, 2, n, C))
+    fb, mb, _ = hz.kvc.chunk_sizes(glo)
+    nc = 2
+    frames = torch.empty(nc * fb, dtype=torch.uint8, device="cuda")
+    meta = torch.empty(nc * mb // 4, dtype=torch.float32, device="cuda")
+    hz.kvc.kvc_pack(glo, big.data_ptr(), (ls, ks, ts), n, frames.data_ptr(), nc * fb, meta.data_ptr(), nc * mb,
+                    hz.stream_handle())
+    torch.cuda.synchronize()
+    want_f, want_m = oracle.pack(olo, kv_synth.to_u16(kv.cpu()).reshape(-1), n)
+    hz.assert_same_bytes("frames", frames.cpu().numpy(), want_f)
+    hz.assert_same_bytes("meta", meta.cpu().numpy().view(np.uint32), want_m.view(np.uint32))
+
+
 def test_paged_bad_block_ids_and_chunked_calls():
     """Ids outside the cache are skipped and reported; chunk-at-a-time calls with first_token fill the same cache."""
     L, H, D, T = 2, 8, 128, 64
@@ -327,13 +351,13 @@ def test_config_llama3_8b_32k_paged():
 
 def test_config_yi34b_80k_paged_bf16():
     w = kv_synth.WORKLOADS["yi34b_80k_paged"]
-    # first chunk, one from the middle, the last full one and the 128-token tail (80000 = 39*2048 + 128)
-    chunkwise_check(w, [0, 19, 38, 39], w.name)
+    # all 40 chunks, the 128-token tail included (80000 = 39*2048 + 128); all 60 layers, K and V
+    chunkwise_check(w, range(w.n_chunks), w.name)
 
 
 def test_config_pipeline_matches_single_call():
-    """16 pinned host blobs, copy on one stream, restore on another: same cache as one kvc_restore_paged call,
-    which the previous tests tie to the oracle; one chunk is also checked against the oracle directly."""
+    """16 pinned host blobs, copy on one stream, restore on another: same cache as one kvc_restore_paged call, and
+    every chunk and layer of the cache the pipeline filled is compared with the oracle's restore of the same blobs."""
     w = kv_synth.WORKLOADS["llama3_8b_32k_pipeline"]
     glo, olo = hz.workload_layouts(w)
     C, T, bs = w.C, w.T, w.block_size
@@ -378,15 +402,27 @@ def test_config_pipeline_matches_single_call():
     torch.cuda.synchronize()
     for l in (0, w.L - 1):
         assert torch.equal(cache.layers[l], ref.layers[l])
-    # oracle on chunk 5 straight from the host blob
-    c = 5
-    blob = blobs[c].numpy()
-    want_caches, err = hz.oracle_paged(olo, blob[:fb], blob[moff:moff + mb].view(np.float32), c * T, T, w.L, n_logical,
-                                       bs, C, table.cpu().numpy())
-    phys = table.cpu().long()[c * T // bs:(c + 1) * T // bs]
-    for l in (0, 13, w.L - 1):
-        got = ref.layers[l][:, phys.cuda()].cpu().numpy().view(np.uint16)
-        hz.assert_same_bytes(f"pipeline chunk {c} layer {l}", got, want_caches[l].reshape(2, n_logical, bs, C)[:, phys.numpy()])
+    # every chunk of the pipeline's own cache against the oracle, which reads the host blobs the pipeline was given
+    oracle_check_cache(w, olo, blobs, fb, moff, mb, table.cpu().numpy(), cache, "chunk pipeline")
+
+
+def oracle_check_cache(w, olo, blobs, fb, moff, mb, table_np, cache, tag):
+    """The oracle restores each chunk from its host blob into a private poison cache; the blocks the chunk owns must
+    equal the same blocks of `cache` (a PagedCache filled on the GPU) in all layers, K and V."""
+    C, T, bs = w.C, w.T, w.block_size
+    n_logical = w.n_logical_blocks
+    for c, b in enumerate(blobs):
+        nt = min(T, w.n_tokens - c * T)
+        blob = b.numpy()
+        want_caches, err = hz.oracle_paged(olo, blob[:fb], blob[moff:moff + mb].view(np.float32), c * T, nt, w.L,
+                                           n_logical, bs, C, table_np)
+        assert err == 0
+        phys = torch.from_numpy(table_np[c * T // bs:(c * T + nt + bs - 1) // bs].astype(np.int64))
+        for l in range(w.L):
+            got = cache.layers[l][:, phys.cuda()].cpu().numpy().view(np.uint16)
+            hz.assert_same_bytes(f"{tag}: chunk {c} layer {l}", got,
+                                 want_caches[l].reshape(2, n_logical, bs, C)[:, phys.numpy()])
+        hz.say(f"[case] {tag}: chunk {c} equals the oracle")
 
 
 # ------------------------------------------------------------------ frame-wise restoration
@@ -462,6 +498,14 @@ def test_frame_ranges_and_small_frame_pipeline(shape, dtype):
     tab = kv_synth.make_block_table(n_logical, nb, 8).cuda()
     ref = hz.PagedCache(L, nb, bs, C)
     hz.gpu_restore_paged(glo, frames, meta, 0, n, ref, tab)
+    # the reference of this test is itself the oracle's result (frames and pairs are bit-exact by the pack tests,
+    # and are compared again here)
+    want_f, want_m = oracle.pack(olo, kv_synth.to_u16(kv.cpu()).reshape(-1), n)
+    hz.assert_same_bytes("frames", frames.cpu().numpy(), want_f)
+    want_caches, oerr = hz.oracle_paged(olo, want_f, want_m, 0, n, L, nb, bs, C, tab.cpu().numpy())
+    assert oerr == 0
+    for l, (got_l, want_l) in enumerate(zip(ref.numpy_layers(), want_caches)):
+        hz.assert_same_bytes(f"chunk-level restore layer {l}", got_l, want_l)
     rng = np.random.default_rng(n)
     got = hz.PagedCache(L, nb, bs, C)
     for c in range(n_chunks):
@@ -634,3 +678,5 @@ def test_config_frame_pipeline_matches_chunk_restore():
         assert int(cache.err.item()) == 0
         for l in range(w.L):
             assert torch.equal(cache.layers[l], ref.layers[l]), f"graph replay {rep}: layer {l}"
+    # the cache the last replay filled, chunk by chunk and layer by layer against the oracle
+    oracle_check_cache(w, olo, blobs, fb, moff, mb, table.cpu().numpy(), cache, "frame pipeline (graph replay)")

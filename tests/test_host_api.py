@@ -254,3 +254,27 @@ def test_bench_contract_pieces_that_need_no_gpu():
     assert pack_bytes == 2 * elems + 16 * fb + pairs == 6_580_862_976
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
+
+
+def test_pack_keeps_strips_resident_only_while_32_bit_row_offsets_hold(kvc_lib):
+    """The register-resident body of kvc_pack addresses all 2048 token rows of a strip with 32-bit byte offsets,
+    whatever the chunk length: a short chunk with a huge token stride (token-major engine tensors) must take the
+    streaming body instead."""
+    C = 1024
+    dense = (2 * 4096 * C, 4096 * C, C)
+    assert kvc.pack_plan(good(), dense) == (1, 1024)
+    assert kvc.pack_plan(good(chunk_tokens=1024, tiles_y=32), dense)[0] == 1
+    assert kvc.pack_plan(good(chunk_tokens=4096, tiles_y=128), dense)[0] == 0          # chunk longer than a strip
+    assert kvc.pack_plan(good(k_mode=1), dense)[0] == 0                                 # nothing per channel
+    # token-major [token][L][2][H][D] with 80 layers of 8192 channels: 2.6 MB between tokens
+    big = good(num_layers=80, num_kv_heads=64, tile_h=64, chunk_tokens=1024, tiles_y=32)
+    Cb = 64 * 128
+    ts = 80 * 2 * Cb
+    assert 1023 * ts * 2 < 2**32 < 2047 * ts * 2   # the chunk's own rows fit, the strip's 2048 rows do not
+    assert kvc.pack_plan(big, (2 * Cb, Cb, ts))[0] == 0
+    # just below / at the limit: 2048 rows * ts * 2 bytes < 2^32
+    edge = 2**32 // (2048 * 2)
+    assert kvc.pack_plan(good(), (8, 8, edge - 8))[0] == 1
+    assert kvc.pack_plan(good(), (8, 8, edge))[0] == 0
+    with pytest.raises(kvc.KvcError):
+        kvc.pack_plan(good(), (0, 0, C - 8))
