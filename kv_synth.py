@@ -104,3 +104,50 @@ def to_u16(t: torch.Tensor):
     import numpy as np
 
     return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def _smooth_along_dim(z, width):
+    """Moving average of `width` neighbours along the last axis (circular), rescaled to unit variance."""
+    acc = torch.zeros_like(z)
+    for s in range(width):
+        acc += torch.roll(z, shifts=s, dims=-1)
+    return acc / math.sqrt(width)
+
+
+def make_kv_correlated(L, H, D, n_tokens, dtype, seed, device="cpu", rho=0.8, mean_power=0.5, head_share=0.5):
+    """Token-correlated stand-in for a real KV cache, for the tiling search (Sec. 3.2.2).
+
+    The i.i.d. recipe of make_kv has no structure a predictive coder could use, so every tiling would look alike.
+    Here, for every (layer, kind), with sigma_c as in make_kv:
+        x[t, h, d] = sigma_c * ( m[h, d] + sqrt(head_share) * g[h, d] * a[t, h] + sqrt(1 - head_share) * e[t, h, d] )
+      m : per-channel mean, variance mean_power, smooth along d inside a head (8-tap moving average of white noise),
+          independent between heads -- channel magnitudes persist over tokens, as in real KV caches;
+      a : one AR(1) series per head (coefficient rho, unit variance): what the elements of a head have in common;
+      g : loading of the head's series on its elements, +-1 with a sign that is smooth along d;
+      e : one AR(1) series per element (coefficient rho, unit variance).
+    With rho = 0.8 and mean_power = 0.5 the correlation over channels between the tensors of consecutive tokens is
+    about (0.5 + 0.8) / 1.5 = 0.87, the similarity the paper reports along the token axis (Appx A.1).
+    Returns [L][2][n_tokens][H][D] of the given torch dtype.  No arithmetic of the method is involved."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    C = H * D
+    sigma = channel_sigmas(L, C, gen, device)                                  # [L][2][C]
+
+    def randn(*shape):
+        return torch.randn(shape, generator=gen, device=device, dtype=torch.float32)
+
+    m = _smooth_along_dim(randn(L, 2, H, D), 8) * math.sqrt(mean_power)
+    g = torch.sign(_smooth_along_dim(randn(L, 2, H, D), 16))
+    g = torch.where(g == 0, torch.ones_like(g), g)
+    kv = torch.empty((L, 2, n_tokens, H, D), dtype=dtype, device=device)
+    innov = math.sqrt(1.0 - rho * rho)
+    a = randn(L, 2, H, 1)
+    e = randn(L, 2, H, D)
+    sa, se = math.sqrt(head_share), math.sqrt(1.0 - head_share)
+    sig = sigma.view(L, 2, H, D)
+    for t in range(n_tokens):
+        if t:
+            a = rho * a + innov * randn(L, 2, H, 1)
+            e = rho * e + innov * randn(L, 2, H, D)
+        kv[:, :, t] = (sig * (m + sa * g * a + se * e)).to(dtype)
+    return kv
