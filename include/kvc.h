@@ -14,8 +14,10 @@
  *     occupy the same tile position in F consecutive frames;
  *   - intra-frame layout (Sec. 3.2.2, rules i-iii and the tiles (8,512),
  *     (8,128), (16,64) found there): the head_num*head_dim vector of one token
- *     and layer is re-tiled row-major into a (tile_h, tile_w) block with no
- *     permutation of heads or of elements inside a head.
+ *     and layer is re-tiled into a (tile_h, tile_w) block with no permutation of
+ *     heads or of elements inside a head: row-major, or as the two-level
+ *     reshape head_num -> (h1, h2), head_dim -> (d1, d2), tile (h1*d1, h2*d2)
+ *     of the section's (32,128) -> (8,4) x (1,128) -> (8,512) example.
  * Fetch side (Sec. 3.3.2 "Frame-wise KV tensor restoration", Sec. 4 item (2)):
  * decoded frames are mapped back to KV tensors, dequantized and written into the
  * preallocated slots of the engine's paged memory.  The H.265 encoder / decoder
@@ -44,7 +46,9 @@
  * ------------
  * frames : [chunk][kind(K=0,V=1)][LG][F][3][Hp][W] uint8, planar.  The byte of
  *          element (kind, l, t, h, d), t local to the chunk, sits at
- *            e = h*D + d ; r = e / tw ; cc = e % tw
+ *            e = h*D + d ; r = e / tw ; cc = e % tw            (tile_seg == 0)
+ *            r = (h / h2)*d1 + d / d2 ; cc = (h % h2)*d2 + d % d2,
+ *              d2 = tile_seg, d1 = D / d2, h2 = tw / d2        (tile_seg  > 0)
  *            f = t % F   ; g = t / F  ; ty = g / TX ; tx = g % TX
  *            y = ty*th + r ; x = tx*tw + cc ; lg = l / 3 ; pl = l % 3
  *          Every byte no valid element maps to (planes of layers >= L, tiles of
@@ -83,7 +87,7 @@
 extern "C" {
 #endif
 
-#define KVC_ABI_VERSION 1u
+#define KVC_ABI_VERSION 2u
 
 typedef enum {
   KVC_OK = 0,
@@ -111,6 +115,11 @@ typedef struct {
   int32_t tiles_y;       /* TY: tiles per frame column (Sec. 3.2.1 observation iii)*/
   int32_t k_mode;        /* kvc_qmode for K (default per channel)                  */
   int32_t v_mode;        /* kvc_qmode for V (default per token)                    */
+  int32_t tile_seg;      /* 0: the tile is the row-major reshape of the H*D vector.
+                            d2 > 0: two-level tiling of Sec. 3.2.2 -- head_num
+                            reshaped to (h1, h2), head_dim to (d1, d2), tile =
+                            (h1*d1, h2*d2); d2 divides D and tile_w, tile_w/d2
+                            divides H; a multiple of 8, else KVC_ERR_UNSUPPORTED */
 } kvc_layout;
 
 /* Strides of a contiguous-style KV tensor [L][2][tokens][H][D], in ELEMENTS.
@@ -353,6 +362,59 @@ double kvc_est_bandwidth(double last_chunk_size, double last_transmission_delay)
 kvc_status kvc_layout_set_resolution(kvc_layout* layout, int32_t width, int32_t height);
 
 /* Static, never-freed description of a status code. */
+/* ---- Intra-frame tiling search (Sec. 3.2.2) -------------------------------
+ * The paper fixes the tile by enumerating the tilings its three rules leave
+ * and measuring the size of the encoded video of each.  The encoder is outside
+ * this library, so the search offered here scores a candidate by a codec-free
+ * proxy instead: the first-order entropy of the residuals a predictive coder
+ * would store, for the predictors a video codec has.  It ranks tilings; it does
+ * not reproduce the paper's compression ratios. */
+
+/* Residuals counted per plane sequence p[f][y][x] (the F frames of one
+ * (chunk, kind, layer); arithmetic modulo 256; pixels outside the plane read 0). */
+typedef enum {
+  KVC_RES_LEFT = 0,      /* p[f][y][x] - p[f][y][x-1]            every frame   */
+  KVC_RES_UP = 1,        /* p[f][y][x] - p[f][y-1][x]            every frame   */
+  KVC_RES_TIME = 2,      /* t = p[f][y][x] - p[f-1][y][x]        frames f >= 1 */
+  KVC_RES_TIME_LEFT = 3, /* t[f][y][x] - t[f][y][x-1]            frames f >= 1 */
+  KVC_RES_TIME_UP = 4    /* t[f][y][x] - t[f][y-1][x]            frames f >= 1 */
+} kvc_residual;
+#define KVC_N_RESIDUALS 5
+
+/* Bytes of the histogram array of n_chunks chunks:
+ * uint64 [n_chunks][2][L][KVC_N_RESIDUALS][256]; (size_t)-1 on a bad argument. */
+size_t kvc_residual_histograms_size(const kvc_layout* layout, int64_t n_chunks);
+
+/* Counts the residuals of every plane sequence of packed chunks (Sec. 3.2.2:
+ * the evaluation step of the tiling search, with the proxy above in place of
+ * the encoder).
+ *   frames   DEVICE in : n_chunks chunk sections as written by kvc_pack
+ *   d_hist   DEVICE out: uint64 [n_chunks][2][L][KVC_N_RESIDUALS][256], every
+ *            entry written (no need to clear it); 8-byte aligned
+ *   hist_cap capacity of d_hist in bytes; too small -> KVC_ERR_BUFFER_TOO_SMALL
+ * KVC_ERR_UNSUPPORTED if one plane sequence has 2^32 pixels or more. */
+kvc_status kvc_residual_histograms(const kvc_layout* layout, const uint8_t* frames, int64_t n_chunks,
+                                   uint64_t* d_hist, size_t hist_cap, void* stream);
+
+/* Cost in bits of n_chunks chunks from their residual histograms (HOST
+ * arithmetic in double).  With H(k) the entropy -sum (n_i/N) log2 (n_i/N) of
+ * histogram k of a plane sequence and P = Hp*W pixels per plane, a sequence costs
+ *   P * min(H(LEFT), H(UP)) + (F-1) * P * min(H(TIME), H(TIME_LEFT), H(TIME_UP)):
+ * the first frame of a group has nothing to predict from in time, the others
+ * take their cheapest predictor.  Returns the sum over all sequences, or a
+ * negative value on a bad argument.
+ *   hist  HOST in: the array kvc_residual_histograms wrote, copied to the host */
+double kvc_proxy_cost_bits(const kvc_layout* layout, const uint64_t* hist, int64_t n_chunks);
+
+/* The tilings left by rules i-iii of Sec. 3.2.2 for H heads of D elements:
+ * head_num = h1*h2 and head_dim = d1*d2 with all four powers of two, tile
+ * (h1*d1, h2*d2), tile_seg = d2 >= 8 (an 8-element atom of the kernels stays in
+ * one row).  Writes up to `cap` candidates in the order h1 ascending, then d1
+ * ascending, and returns how many there are (which may exceed cap); -1 on a bad
+ * argument.  HOST. */
+int32_t kvc_tile_candidates(int32_t num_kv_heads, int32_t head_dim, int32_t* tile_h, int32_t* tile_w,
+                            int32_t* tile_seg, int32_t cap);
+
 const char* kvc_status_str(kvc_status status);
 
 /* Identifier of what this binary was built from: a hash of the library's

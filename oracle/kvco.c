@@ -19,21 +19,16 @@
 
 static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-/* d2 of Sec. 3.2.2's two-level reshape: how many consecutive elements of a head share a tile row. */
-int64_t kvco_segment(const kvco_layout* lo) {
-  if (lo->seg != 0) return lo->seg;
-  return lo->tw < lo->D ? lo->tw : lo->D; /* plain row-major retile of the H*D vector */
-}
-
 int kvco_check(const kvco_layout* lo) {
   if (!lo) return 1;
   if (lo->L < 1 || lo->H < 1 || lo->D < 1 || lo->T < 1) return 1;
   if (lo->th < 1 || lo->tw < 1 || lo->TX < 1 || lo->TY < 1) return 1;
   if ((int64_t)lo->th * lo->tw != (int64_t)lo->H * lo->D) return 1; /* Sec. 3.2.2: a tile is a reshape of the H*D vector */
-  {
+  if (lo->seg < 0) return 1;
+  if (lo->seg > 0) {
     /* Sec. 3.2.2: head_dim = d1 * d2 and head_num = h1 * h2 with tile = (h1*d1, h2*d2) */
-    const int64_t d2 = kvco_segment(lo);
-    if (d2 < 1 || lo->D % d2 != 0 || lo->tw % d2 != 0) return 1;
+    const int64_t d2 = lo->seg;
+    if (lo->D % d2 != 0 || lo->tw % d2 != 0) return 1;
     if (lo->H % (lo->tw / d2) != 0) return 1;
     if ((int64_t)(lo->H / (lo->tw / d2)) * (lo->D / d2) != lo->th) return 1;
   }
@@ -73,14 +68,21 @@ int64_t kvco_frame_offset(const kvco_layout* lo, int kind, int l, int64_t t, int
   const int64_t F = kvco_frames_per_group(lo);
   const int64_t W = (int64_t)lo->TX * lo->tw;
   /* Sec. 3.2.2: heads in initial order (rule iii), elements of a head in order (rule ii), no mixing of heads
-   * (rule i); head_num is reshaped to (h1, h2) and head_dim to (d1, d2), and the tile is (h1*d1, h2*d2):
-   * head h = a*h2 + b, element d = c*d2 + i  ->  row a*d1 + c, column b*d2 + i.  With d1 = 1 or h2 = 1 this
-   * is the row-major reshape of the H*D vector to (th, tw). */
-  const int64_t d2 = kvco_segment(lo);
-  const int64_t d1 = lo->D / d2;
-  const int64_t h2 = lo->tw / d2;
-  const int64_t r = (h / h2) * d1 + d / d2;
-  const int64_t cc = (h % h2) * d2 + d % d2;
+   * (rule i).  seg = 0: the H*D vector of the token reshaped row-major to (th, tw).  seg = d2 > 0: head_num is
+   * reshaped to (h1, h2) and head_dim to (d1, d2), and the tile is (h1*d1, h2*d2): head h = a*h2 + b, element
+   * d = c*d2 + i  ->  row a*d1 + c, column b*d2 + i (with d1 = 1 or h2 = 1 that is the row-major reshape again). */
+  int64_t r, cc;
+  if (lo->seg == 0) {
+    const int64_t e = (int64_t)h * lo->D + d;
+    r = e / lo->tw;
+    cc = e % lo->tw;
+  } else {
+    const int64_t d2 = lo->seg;
+    const int64_t d1 = lo->D / d2;
+    const int64_t h2 = lo->tw / d2;
+    r = (h / h2) * d1 + d / d2;
+    cc = (h % h2) * d2 + d % d2;
+  }
   /* Sec. 3.2.1 steps 2-3: token t is tensor number t % F of group t / F; the
    * tensors of a group share one tile position in F consecutive frames.  Tile
    * positions are taken in raster order over the TX x TY grid. */

@@ -46,12 +46,12 @@ typedef struct {
   int32_t TX, TY;       /* tile grid of one frame                         */
   int32_t k_mode;       /* 0 = one group per channel per chunk            */
   int32_t v_mode;       /* 1 = one group per (token, head)                */
-  int32_t seg;          /* d2: consecutive elements of one head per tile row;
-                           0 = the row-major retile, min(D, tw)             */
+  int32_t seg;          /* 0: tile = row-major reshape of the H*D vector;
+                           d2 > 0: two-level tiling, d2 consecutive elements
+                           of one head per tile row                         */
 } kvco_layout;
 
 int kvco_check(const kvco_layout* lo);                       /* 0 if consistent */
-int64_t kvco_segment(const kvco_layout* lo);                 /* d2 (resolves seg = 0) */
 int64_t kvco_frames_per_group(const kvco_layout* lo);        /* F  */
 int64_t kvco_frame_bytes(const kvco_layout* lo);             /* per chunk */
 int64_t kvco_meta_floats(const kvco_layout* lo);             /* per chunk, in floats */

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <limits.h>
+#include <math.h>
 #include <string.h>
 
 #include <vector>
@@ -23,6 +24,14 @@ kvc_status check_layout(const kvc_layout* lo) {
   if (lo->num_layers < 1 || lo->num_kv_heads < 1 || lo->head_dim < 1 || lo->chunk_tokens < 1) return KVC_ERR_INVALID_ARG;
   if (lo->tile_h < 1 || lo->tile_w < 1 || lo->tiles_x < 1 || lo->tiles_y < 1) return KVC_ERR_INVALID_ARG;
   if ((int64_t)lo->tile_h * lo->tile_w != (int64_t)lo->num_kv_heads * lo->head_dim) return KVC_ERR_INVALID_ARG;
+  if (lo->tile_seg < 0) return KVC_ERR_INVALID_ARG;
+  if (lo->tile_seg > 0) {  // Sec. 3.2.2: head_num = h1 * h2, head_dim = d1 * d2, tile = (h1 * d1, h2 * d2)
+    const int32_t d2 = lo->tile_seg;
+    if (lo->head_dim % d2 != 0 || lo->tile_w % d2 != 0) return KVC_ERR_INVALID_ARG;
+    const int32_t h2 = lo->tile_w / d2;
+    if (lo->num_kv_heads % h2 != 0) return KVC_ERR_INVALID_ARG;
+    if ((int64_t)(lo->num_kv_heads / h2) * (lo->head_dim / d2) != lo->tile_h) return KVC_ERR_INVALID_ARG;
+  }
   if (lo->dtype != KVC_F16 && lo->dtype != KVC_BF16) return KVC_ERR_INVALID_ARG;
   if (lo->k_mode != KVC_Q_PER_CHANNEL && lo->k_mode != KVC_Q_PER_TOKEN) return KVC_ERR_INVALID_ARG;
   if (lo->v_mode != KVC_Q_PER_CHANNEL && lo->v_mode != KVC_Q_PER_TOKEN) return KVC_ERR_INVALID_ARG;
@@ -37,6 +46,20 @@ kvc_status check_layout(const kvc_layout* lo) {
 }
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// Entropy in bits per symbol of a 256-bin histogram (0 for an empty one).
+double histogram_entropy(const uint64_t* bins) {
+  double n = 0.0;
+  for (int i = 0; i < 256; ++i) n += (double)bins[i];
+  if (n == 0.0) return 0.0;
+  double h = 0.0;
+  for (int i = 0; i < 256; ++i)
+    if (bins[i]) {
+      const double q = (double)bins[i] / n;
+      h -= q * log2(q);
+    }
+  return h;
+}
 
 // Lowest index at which cost(i), i in [0, n), is smallest.
 template <typename Cost>
@@ -64,7 +87,7 @@ kvc_status check_strides(const kvc_strides& s) {
 kvc_status make_geo(const kvc_layout* lo, Geo* g) {
   const kvc_status st = check_layout(lo);
   if (st != KVC_OK) return st;
-  if (lo->head_dim % 8 != 0 || lo->tile_w % 8 != 0) return KVC_ERR_UNSUPPORTED;
+  if (lo->head_dim % 8 != 0 || lo->tile_w % 8 != 0 || lo->tile_seg % 8 != 0) return KVC_ERR_UNSUPPORTED;
   g->L = lo->num_layers;
   g->H = lo->num_kv_heads;
   g->D = lo->head_dim;
@@ -96,6 +119,10 @@ kvc_status make_geo(const kvc_layout* lo, Geo* g) {
   g->dTX = make_fastdiv((uint32_t)g->TX);
   g->dtw = make_fastdiv((uint32_t)g->tw);
   g->dD = make_fastdiv((uint32_t)g->D);
+  g->seg = lo->tile_seg;
+  g->d1 = g->seg ? g->D / g->seg : 1;
+  g->dseg = make_fastdiv((uint32_t)(g->seg ? g->seg : 1));
+  g->dh2 = make_fastdiv((uint32_t)(g->seg ? g->tw / g->seg : 1));
   return KVC_OK;
 }
 
@@ -251,6 +278,64 @@ kvc_status kvc_restore_paged(const kvc_layout* layout, const uint8_t* frames, co
   p.frames = frames;
   p.meta = static_cast<const float*>(meta);
   return launch_restore(p, true, as_stream(stream));
+}
+
+size_t kvc_residual_histograms_size(const kvc_layout* layout, int64_t n_chunks) {
+  if (check_layout(layout) != KVC_OK || n_chunks < 0 || n_chunks > (1 << 24)) return (size_t)-1;
+  return (size_t)n_chunks * 2 * (size_t)layout->num_layers * KVC_N_RESIDUALS * 256 * sizeof(uint64_t);
+}
+
+kvc_status kvc_residual_histograms(const kvc_layout* layout, const uint8_t* frames, int64_t n_chunks, uint64_t* d_hist,
+                                   size_t hist_cap, void* stream) {
+  ScoreParams p{};
+  const kvc_status st = make_geo(layout, &p.g);
+  if (st != KVC_OK) return st;
+  if (n_chunks < 0 || n_chunks > (1 << 24)) return KVC_ERR_INVALID_ARG;
+  if (n_chunks == 0) return KVC_OK;
+  if (!frames || !d_hist || !aligned(frames, 8) || !aligned(d_hist, 8)) return KVC_ERR_INVALID_ARG;
+  if (kvc_residual_histograms_size(layout, n_chunks) > hist_cap) return KVC_ERR_BUFFER_TOO_SMALL;
+  p.frames = frames;
+  p.n_chunks = (int32_t)n_chunks;
+  p.hist = d_hist;
+  return launch_residual_histograms(p, as_stream(stream));
+}
+
+double kvc_proxy_cost_bits(const kvc_layout* layout, const uint64_t* hist, int64_t n_chunks) {
+  Geo g;
+  if (make_geo(layout, &g) != KVC_OK || !hist || n_chunks < 0) return -1.0;
+  const double pixels = (double)g.plane;
+  double total = 0.0;
+  for (int64_t s = 0; s < n_chunks * 2 * g.L; ++s) {
+    double h[KVC_N_RESIDUALS];
+    for (int k = 0; k < KVC_N_RESIDUALS; ++k) h[k] = histogram_entropy(hist + (s * KVC_N_RESIDUALS + k) * 256);
+    total += pixels * (h[KVC_RES_LEFT] < h[KVC_RES_UP] ? h[KVC_RES_LEFT] : h[KVC_RES_UP]);
+    if (g.F > 1) {
+      double inter = h[KVC_RES_TIME];
+      if (h[KVC_RES_TIME_LEFT] < inter) inter = h[KVC_RES_TIME_LEFT];
+      if (h[KVC_RES_TIME_UP] < inter) inter = h[KVC_RES_TIME_UP];
+      total += (double)(g.F - 1) * pixels * inter;
+    }
+  }
+  return total;
+}
+
+int32_t kvc_tile_candidates(int32_t num_kv_heads, int32_t head_dim, int32_t* tile_h, int32_t* tile_w, int32_t* tile_seg,
+                            int32_t cap) {
+  if (num_kv_heads < 1 || head_dim < 1 || cap < 0 || (cap > 0 && (!tile_h || !tile_w || !tile_seg))) return -1;
+  int32_t n = 0;
+  for (int64_t h1 = 1; h1 <= num_kv_heads; h1 *= 2) {
+    if (num_kv_heads % h1 != 0) continue;
+    for (int64_t d1 = 1; d1 <= head_dim; d1 *= 2) {
+      if (head_dim % d1 != 0 || head_dim / d1 < 8) continue;
+      if (n < cap) {
+        tile_h[n] = (int32_t)(h1 * d1);
+        tile_w[n] = (int32_t)((num_kv_heads / h1) * (head_dim / d1));
+        tile_seg[n] = (int32_t)(head_dim / d1);
+      }
+      ++n;
+    }
+  }
+  return n;
 }
 
 size_t kvc_frame_size(const kvc_layout* layout) {

@@ -54,6 +54,7 @@ KVC_HD void fd_divmod(const FastDiv& f, uint32_t n, uint32_t& q, uint32_t& r) {
 struct Geo {
   int32_t L, H, D, C, T;
   int32_t th, tw, TX, TY;
+  int32_t seg, d1;       // two-level tile: run length d2 (0: row-major retile) and runs per head
   int32_t F, LG, W, Hp;
   int32_t G;             // TX*TY tile positions per frame
   int32_t FG;            // F*G >= T token positions per chunk
@@ -65,7 +66,22 @@ struct Geo {
   int64_t meta_floats;   // per chunk
   int64_t meta_off[2];   // float offset of the K / V block inside a chunk's meta
   FastDiv dF, dTX, dtw, dD;
+  FastDiv dseg, dh2;     // two-level tile: run length, heads side by side in a tile row
 };
+
+// Intra-frame layout (Sec. 3.2.2): first element e of an atom -> (row, column) inside the token's tile.
+KVC_HD void tile_pos(const Geo& g, uint32_t e, uint32_t& r, uint32_t& cc) {
+  if (g.seg == 0) {
+    fd_divmod(g.dtw, e, r, cc);  // row-major reshape of the H*D vector
+  } else {
+    uint32_t h, d, a, b, c, i;
+    fd_divmod(g.dD, e, h, d);
+    fd_divmod(g.dh2, h, a, b);   // head = a * h2 + b
+    fd_divmod(g.dseg, d, c, i);  // element of the head = c * d2 + i
+    r = a * (uint32_t)g.d1 + c;
+    cc = b * (uint32_t)g.seg + i;
+  }
+}
 
 // Fills `g` from a validated layout.  Returns KVC_OK or the reason the kernels
 // cannot take it.

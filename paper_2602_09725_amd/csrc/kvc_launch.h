@@ -84,4 +84,16 @@ kvc_status plan_pack(PackParams& p, int* threads_out);
 // unused planes and tile positions.
 kvc_status launch_pack(PackParams p, hipStream_t stream);
 
+struct ScoreParams {
+  Geo g;
+  const uint8_t* frames;  // chunk sections
+  int32_t n_chunks;
+  uint64_t* hist;         // [n_chunks][2][L][KVC_N_RESIDUALS][256]
+  FastDiv dL;             // stream -> (chunk, kind), layer
+  FastDiv dper_row;       // 8-pixel pieces per plane row
+};
+
+// Enqueues the residual-histogram kernel of the tiling proxy: one workgroup per (chunk, kind, layer).
+kvc_status launch_residual_histograms(ScoreParams p, hipStream_t stream);
+
 }  // namespace kvc

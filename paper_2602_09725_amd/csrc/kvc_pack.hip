@@ -249,7 +249,7 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
   const int32_t t1 = t0 + p.tb < g.FG ? t0 + p.tb : g.FG;
 
   uint32_t r, cc;
-  fd_divmod(g.dtw, e, r, cc);
+  tile_pos(g, e, r, cc);
   const uint32_t lg = l / 3u, pl = l - lg * 3u;
   uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane +
                    (r * (uint32_t)g.W + cc);
@@ -358,7 +358,7 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
   if (l >= (uint32_t)g.L) n = 0;
 
   uint32_t r, cc;
-  fd_divmod(g.dtw, e, r, cc);
+  tile_pos(g, e, r, cc);
   const uint32_t lg = l / 3u, pl = l - lg * 3u;
   uint8_t* fbase = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane +
                    (r * (uint32_t)g.W + cc);
@@ -487,7 +487,7 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
   if (l >= (uint32_t)g.L) n = 0;
 
   uint32_t r, cc;
-  fd_divmod(g.dtw, e, r, cc);
+  tile_pos(g, e, r, cc);
   const uint32_t lg = l / 3u, pl = l - lg * 3u;
   uint8_t* fplane = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane;
   const uint8_t* srcb = reinterpret_cast<const uint8_t*>(p.kv + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts);

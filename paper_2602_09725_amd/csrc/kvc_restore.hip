@@ -137,7 +137,7 @@ __device__ __forceinline__ void restore_body_waves(const RestoreParams& p, uint3
 
   // ---- per-lane constants
   uint32_t r, cc;
-  fd_divmod(g.dtw, e, r, cc);  // intra-frame layout: element -> (row, column) of the tile
+  tile_pos(g, e, r, cc);  // intra-frame layout: element -> (row, column) of the tile
   const uint32_t src_lane = r * (uint32_t)g.W + cc;
   const float* mbase = p.meta + (int64_t)c * g.meta_floats + p.moff[kind];
   const uint32_t lm = l - (uint32_t)p.meta_l0;  // layer index inside the pairs that `meta` holds
@@ -195,7 +195,7 @@ __device__ __forceinline__ void restore_body_lanes(const RestoreParams& p, uint3
   if (t0 >= t1) return;
 
   uint32_t r, cc;
-  fd_divmod(g.dtw, e, r, cc);
+  tile_pos(g, e, r, cc);
   const uint8_t* fbase = fsec + (r * (uint32_t)g.W + cc);
   const float* mbase = p.meta + (int64_t)c * g.meta_floats + p.moff[kind];
   const uint32_t lm = l - (uint32_t)p.meta_l0;  // layer index inside the pairs that `meta` holds

@@ -9,7 +9,7 @@ import os
 KVC_F16, KVC_BF16 = 0, 1
 KVC_Q_PER_CHANNEL, KVC_Q_PER_TOKEN = 0, 1
 KVC_ORDER_CHUNK, KVC_ORDER_LAYER = 0, 1
-KVC_ABI_VERSION = 1
+KVC_ABI_VERSION = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libkvc.so")
@@ -26,12 +26,12 @@ class Layout(C.Structure):
     """kvc_layout"""
     _fields_ = [("struct_size", C.c_uint32), ("abi_version", C.c_uint32)] + [
         (n, C.c_int32) for n in ("num_layers", "num_kv_heads", "head_dim", "dtype", "chunk_tokens", "tile_h", "tile_w",
-                                 "tiles_x", "tiles_y", "k_mode", "v_mode")]
+                                 "tiles_x", "tiles_y", "k_mode", "v_mode", "tile_seg")]
 
     def __init__(self, num_layers, num_kv_heads, head_dim, dtype, chunk_tokens, tile_h, tile_w, tiles_x, tiles_y,
-                 k_mode=KVC_Q_PER_CHANNEL, v_mode=KVC_Q_PER_TOKEN):
+                 k_mode=KVC_Q_PER_CHANNEL, v_mode=KVC_Q_PER_TOKEN, tile_seg=0):
         super().__init__(C.sizeof(Layout), KVC_ABI_VERSION, num_layers, num_kv_heads, head_dim, dtype, chunk_tokens,
-                         tile_h, tile_w, tiles_x, tiles_y, k_mode, v_mode)
+                         tile_h, tile_w, tiles_x, tiles_y, k_mode, v_mode, tile_seg)
 
 
 class Strides(C.Structure):
@@ -94,6 +94,14 @@ def load(path=None):
     lib.kvc_admission_ok.restype = i32
     lib.kvc_admission_min_buffered.argtypes = [dp, dp, i32]
     lib.kvc_admission_min_buffered.restype = i32
+    lib.kvc_residual_histograms_size.argtypes = [LP, i64]
+    lib.kvc_residual_histograms_size.restype = sz
+    lib.kvc_residual_histograms.argtypes = [LP, vp, i64, vp, sz, vp]
+    lib.kvc_proxy_cost_bits.argtypes = [LP, vp, i64]
+    lib.kvc_proxy_cost_bits.restype = C.c_double
+    ip = C.POINTER(i32)
+    lib.kvc_tile_candidates.argtypes = [i32, i32, ip, ip, ip, i32]
+    lib.kvc_tile_candidates.restype = i32
     if path is None:
         _lib = lib
     return lib
@@ -149,6 +157,33 @@ def kvc_restore_paged(layout, frames_ptr, meta_ptr, first_token, n_tokens, layer
     _check(load().kvc_restore_paged(C.byref(layout), frames_ptr, meta_ptr, first_token, n_tokens,
                                     layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr, table_len, err_ptr,
                                     stream), "kvc_restore_paged")
+
+
+N_RESIDUALS = 5
+
+
+def residual_histograms_size(layout, n_chunks):
+    return load().kvc_residual_histograms_size(C.byref(layout), n_chunks)
+
+
+def kvc_residual_histograms(layout, frames_ptr, n_chunks, hist_ptr, hist_cap, stream=0):
+    _check(load().kvc_residual_histograms(C.byref(layout), frames_ptr, n_chunks, hist_ptr, hist_cap, stream),
+           "kvc_residual_histograms")
+
+
+def proxy_cost_bits(layout, hist_host_ptr, n_chunks):
+    """hist_host_ptr: address of the uint64 histogram array in host memory."""
+    return load().kvc_proxy_cost_bits(C.byref(layout), hist_host_ptr, n_chunks)
+
+
+def tile_candidates(num_kv_heads, head_dim):
+    """-> [(tile_h, tile_w, tile_seg)] of the tilings rules i-iii of Sec. 3.2.2 leave."""
+    n = load().kvc_tile_candidates(num_kv_heads, head_dim, None, None, None, 0)
+    if n < 0:
+        raise KvcError(1, "kvc_tile_candidates")
+    th, tw, seg = (C.c_int32 * n)(), (C.c_int32 * n)(), (C.c_int32 * n)()
+    load().kvc_tile_candidates(num_kv_heads, head_dim, th, tw, seg, n)
+    return [(th[i], tw[i], seg[i]) for i in range(n)]
 
 
 def kvc_fetch_pipeline(layout, chunks, staging_ptrs, staging_bytes, layer_cache_ptrs_dev, num_blocks, block_size,

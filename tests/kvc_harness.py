@@ -19,11 +19,11 @@ def say(msg):
     sys.stdout.flush()
 
 
-def layouts(L, H, D, dtype, T, th, tw, TX, TY, k_mode=0, v_mode=1):
-    """(GPU layout, oracle layout) with the same geometry; dtype is 'f16' | 'bf16'."""
+def layouts(L, H, D, dtype, T, th, tw, TX, TY, k_mode=0, v_mode=1, seg=0):
+    """(GPU layout, oracle layout) with the same geometry; dtype is 'f16' | 'bf16'; seg = d2 of a two-level tile."""
     dt = 0 if dtype == "f16" else 1
-    return (kvc.Layout(L, H, D, dt, T, th, tw, TX, TY, k_mode, v_mode),
-            oracle.make_layout(L, H, D, dt, T, th, tw, TX, TY, k_mode, v_mode))
+    return (kvc.Layout(L, H, D, dt, T, th, tw, TX, TY, k_mode, v_mode, seg),
+            oracle.make_layout(L, H, D, dt, T, th, tw, TX, TY, k_mode, v_mode, seg))
 
 
 def workload_layouts(w, L=None):

@@ -186,6 +186,22 @@ def test_adversarial_values(dtype, modes):
     full_check(glo, olo, kv, n, dtype, block_size=16, tag="adversarial")
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("modes", [(0, 1), (1, 0)], ids=["Kc_Vt", "Kt_Vc"])
+@pytest.mark.parametrize("H,D,h1,d1", [(8, 128, 4, 2), (8, 128, 2, 4), (8, 128, 1, 16), (8, 128, 8, 2), (32, 128, 8, 4),
+                                       (4, 64, 2, 8), (6, 16, 3, 2)])
+def test_two_level_tiles(H, D, h1, d1, modes, dtype):
+    """Sec. 3.2.2: head_num -> (h1, h2), head_dim -> (d1, d2), tile (h1*d1, h2*d2), the members that are not a
+    row-major reshape included; pack, restore and paged restore against the oracle, ragged last chunk."""
+    h2, d2 = H // h1, D // d1
+    th, tw = h1 * d1, h2 * d2
+    L, T, TX, TY = 4, 40, 2, 5
+    n = T + 13
+    glo, olo = hz.layouts(L, H, D, dtype, T, th, tw, TX, TY, modes[0], modes[1], seg=d2)
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=300 + h1 * 17 + d1, device="cuda")
+    full_check(glo, olo, kv, n, dtype, block_size=16, tag=f"two-level tile ({h1},{h2})x({d1},{d2})")
+
+
 def test_strided_input_and_output():
     L, H, D, T, n = 3, 4, 32, 32, 32 + 9
     C = H * D

@@ -36,13 +36,13 @@ def test_library_exports_every_declared_symbol(kvc_lib):
 
 
 def test_binding_struct_matches_header(kvc_lib):
-    assert ctypes.sizeof(kvc.Layout) == 13 * 4
+    assert ctypes.sizeof(kvc.Layout) == 14 * 4
     assert kvc.layout_validate(good()) == 0
     lo = good()
     lo.struct_size = 48
     assert kvc.layout_validate(lo) == 1
     lo = good()
-    lo.abi_version = 2
+    lo.abi_version = 1
     assert kvc.layout_validate(lo) == 1
 
 
@@ -59,11 +59,27 @@ def test_chunk_sizes_agree_with_oracle(kvc_lib, oracle):
 
 
 @pytest.mark.parametrize("kw", [dict(tile_w=100), dict(num_layers=0), dict(dtype=2), dict(k_mode=3), dict(tiles_x=0),
-                                dict(chunk_tokens=-5), dict(tile_h=16)])
+                                dict(chunk_tokens=-5), dict(tile_h=16), dict(tile_seg=-8), dict(tile_seg=48),
+                                dict(tile_seg=256), dict(tile_h=1, tile_w=1024, tile_seg=64)])
 def test_inconsistent_layouts_rejected(kvc_lib, kw):
     assert kvc.layout_validate(good(**kw)) == 1
     with pytest.raises(kvc.KvcError):
         kvc.chunk_sizes(good(**kw))
+
+
+def test_two_level_tiles_validate_like_the_oracle(kvc_lib, oracle):
+    """tile_seg = d2 of Sec. 3.2.2's two-level reshape: accepted exactly when the oracle accepts it; a run shorter than
+    an 8-element atom is a valid layout the kernels do not cover."""
+    for th, tw, seg in [(8, 128, 64), (16, 64, 16), (8, 128, 128), (8, 128, 0), (4, 256, 32), (8, 128, 48),
+                        (8, 128, 256), (1, 1024, 64), (32, 32, 32), (64, 16, 16)]:
+        lo = good(tile_h=th, tile_w=tw, tile_seg=seg)
+        olo = oracle.make_layout(32, 8, 128, 0, 2048, th, tw, 8, 64, seg=seg)
+        assert (kvc.layout_validate(lo) == 0) == (oracle.lib().kvco_check(olo) == 0), (th, tw, seg)
+    lo = good(tile_h=128, tile_w=8, tile_seg=4)   # heads (4,2), dims (32,4)
+    assert kvc.layout_validate(lo) == 0
+    with pytest.raises(kvc.KvcError) as e:
+        kvc.pack_plan(lo, (2 * 4096 * 1024, 4096 * 1024, 1024))
+    assert e.value.status == 2
 
 
 def test_data_calls_reject_bad_arguments_before_enqueueing(kvc_lib):
@@ -278,3 +294,49 @@ def test_pack_keeps_strips_resident_only_while_32_bit_row_offsets_hold(kvc_lib):
     assert kvc.pack_plan(good(), (8, 8, edge))[0] == 0
     with pytest.raises(kvc.KvcError):
         kvc.pack_plan(good(), (0, 0, C - 8))
+
+
+def test_tile_candidates_equal_the_oracles_enumeration(kvc_lib):
+    from oracle import residuals as R
+
+    for H, D in [(8, 128), (32, 128), (1, 8), (6, 16), (40, 96)]:
+        assert kvc.tile_candidates(H, D) == R.tile_candidates(H, D)
+    for th, tw, seg in kvc.tile_candidates(8, 128):
+        assert kvc.layout_validate(good(tile_h=th, tile_w=tw, tile_seg=seg)) == 0
+    assert kvc_lib.kvc_tile_candidates(0, 128, None, None, None, 0) == -1
+    assert kvc_lib.kvc_tile_candidates(8, 128, None, None, None, 4) == -1
+
+
+def test_proxy_cost_equals_the_oracle_on_random_histograms(kvc_lib, oracle):
+    """kvc_proxy_cost_bits is host arithmetic: same histograms in, same bits out as oracle/residuals.py (both sum
+    -n log2(n/N) in double; the summation order differs, hence a relative tolerance of 1e-12)."""
+    from oracle import residuals as R
+
+    rng = np.random.default_rng(5)
+    for kw, n_chunks in ((dict(num_layers=3, chunk_tokens=40, tiles_x=2, tiles_y=5), 2),
+                         (dict(num_layers=2, chunk_tokens=16, tiles_x=4, tiles_y=4), 1)):    # F = 4 and F = 1
+        lo = good(**kw)
+        olo = oracle.make_layout(lo.num_layers, 8, 128, 0, lo.chunk_tokens, 8, 128, lo.tiles_x, lo.tiles_y)
+        shape = (n_chunks, 2, lo.num_layers, R.N_RESIDUALS, 256)
+        hist = rng.integers(0, 1000, size=shape).astype(np.uint64)
+        hist[0, 0, 0, 0] = 0
+        hist[0, 0, 0, 0, 17] = 12345            # a constant residual: entropy 0
+        hist[0, 1, 1, 2] = 0                    # an empty histogram
+        assert kvc.residual_histograms_size(lo, n_chunks) == hist.nbytes
+        got = kvc.proxy_cost_bits(lo, hist.ctypes.data, n_chunks)
+        want = R.total_cost_bits(olo, hist)
+        assert abs(got - want) <= 1e-12 * want
+    assert kvc.proxy_cost_bits(good(), None, 1) < 0
+
+
+def test_residual_histograms_reject_bad_arguments(kvc_lib):
+    lo = good()
+    A = 0x7F0000000000
+    need = kvc.residual_histograms_size(lo, 2)
+    assert need == 2 * 2 * 32 * 5 * 256 * 8
+    for args, status in (((A, 2, A, need - 8), 3), ((0, 2, A, need), 1), ((A, 2, 0, need), 1), ((A + 4, 2, A, need), 1),
+                         ((A, -1, A, need), 1)):
+        with pytest.raises(kvc.KvcError) as e:
+            kvc.kvc_residual_histograms(lo, *args)
+        assert e.value.status == status
+    kvc.kvc_residual_histograms(lo, A, 0, A, 0)   # nothing to do: returns before anything is enqueued
