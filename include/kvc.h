@@ -68,7 +68,10 @@
  * Pointers marked DEVICE must be device memory valid on the current HIP device;
  * pointers marked HOST are ordinary host memory (PINNED where stated).  The
  * caller owns every buffer; the library allocates no device memory and keeps no
- * reference after a call returns.  Data calls enqueue work on the given stream
+ * reference to a caller's buffer after a call returns.  Its only state is a
+ * per-device pool of HIP events that the two fetch pipelines borrow from: the
+ * events are created on first use, reused by later calls and released when the
+ * process ends.  Data calls enqueue work on the given stream
  * (a hipStream_t passed as void*, NULL = the default stream) and return without
  * synchronizing unless stated.  Every host-checkable fault returns an error
  * code before anything is enqueued; nothing throws across the ABI.  Calls are

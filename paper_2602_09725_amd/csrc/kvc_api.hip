@@ -6,6 +6,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "kvc_launch.h"
@@ -407,28 +408,55 @@ int64_t pairs_per_layer(const Geo& g, int kind) {
   return g.mode[kind] == KVC_Q_PER_CHANNEL ? (int64_t)g.C : (int64_t)g.T * g.H;
 }
 
-// Events of one staging ring: "copied" after the H2D copy into a slot, "freed"
-// after the last kernel that read it.
-struct Ring {
-  hipEvent_t copied[64], freed[64];
-  int n = 0;
-  bool create(int slots) {
-    for (; n < slots; ++n) {
-      if (hipEventCreateWithFlags(&copied[n], hipEventDisableTiming) != hipSuccess) return false;
-      if (hipEventCreateWithFlags(&freed[n], hipEventDisableTiming) != hipSuccess) {
-        (void)hipEventDestroy(copied[n]);
-        return false;
+// HIP events of the fetch pipelines.  Creating and destroying events costs host time in front of every
+// fetch, so the library keeps the events it has made, per device, for the life of the process: a call borrows
+// what it needs and hands it back when it returns.  Handing back right after the work is enqueued is safe: a
+// wait enqueued on a stream refers to the record that preceded it, not to later records of the same event, and
+// an elapsed time is read before the call returns.
+constexpr int kMaxDevices = 64;
+std::mutex pool_mutex;
+std::vector<hipEvent_t> pool_sync[kMaxDevices], pool_timed[kMaxDevices];
+
+class EventLease {
+ public:
+  EventLease(int n_sync, int n_timed) {
+    if (hipGetDevice(&device_) != hipSuccess || device_ < 0 || device_ >= kMaxDevices) {
+      device_ = -1;
+      return;
+    }
+    ok_ = take(pool_sync[device_], n_sync, hipEventDisableTiming, sync_) && take(pool_timed[device_], n_timed, hipEventDefault, timed_);
+  }
+  ~EventLease() {
+    if (device_ < 0) return;
+    std::lock_guard<std::mutex> lock(pool_mutex);
+    pool_sync[device_].insert(pool_sync[device_].end(), sync_.begin(), sync_.end());
+    pool_timed[device_].insert(pool_timed[device_].end(), timed_.begin(), timed_.end());
+  }
+  EventLease(const EventLease&) = delete;
+  EventLease& operator=(const EventLease&) = delete;
+  bool ok() const { return ok_; }
+  hipEvent_t sync(int i) const { return sync_[i]; }
+  hipEvent_t timed(int i) const { return timed_[i]; }
+
+ private:
+  static bool take(std::vector<hipEvent_t>& pool, int n, unsigned flags, std::vector<hipEvent_t>& out) {
+    {
+      std::lock_guard<std::mutex> lock(pool_mutex);
+      while ((int)out.size() < n && !pool.empty()) {
+        out.push_back(pool.back());
+        pool.pop_back();
       }
+    }
+    while ((int)out.size() < n) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreateWithFlags(&e, flags) != hipSuccess) return false;  // what was taken goes back in the destructor
+      out.push_back(e);
     }
     return true;
   }
-  void destroy() {
-    for (int i = 0; i < n; ++i) {
-      (void)hipEventDestroy(copied[i]);
-      (void)hipEventDestroy(freed[i]);
-    }
-    n = 0;
-  }
+  int device_ = -1;
+  bool ok_ = false;
+  std::vector<hipEvent_t> sync_, timed_;
 };
 
 }  // namespace
@@ -488,17 +516,15 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
 
   hipStream_t cs = as_stream(copy_stream), xs = as_stream(compute_stream);
   const bool blocking = fetch_to_ready_ms || group_ready_ms;
-  Ring frames_ring, meta_ring;
-  hipEvent_t t_begin = nullptr, t_end = nullptr;
-  std::vector<hipEvent_t> t_group;  // timing events of the layer groups
-  bool ok = frames_ring.create(n_frame_staging) && meta_ring.create(n_meta_staging);
-  if (ok && blocking) ok = hipEventCreate(&t_begin) == hipSuccess && hipEventCreate(&t_end) == hipSuccess;
-  if (ok && group_ready_ms)
-    for (int lg = 0; lg < g.LG && ok; ++lg) {
-      hipEvent_t e = nullptr;
-      ok = hipEventCreate(&e) == hipSuccess;
-      if (ok) t_group.push_back(e);
-    }
+  // "copied" after the copies into a frame slot, "freed" after the last kernel that read a slot (frame slots, then
+  // meta slots); with timing: begin, end, then one per layer group
+  EventLease ev(2 * n_frame_staging + n_meta_staging, blocking ? 2 + (group_ready_ms ? g.LG : 0) : 0);
+  bool ok = ev.ok();
+  const auto frames_copied = [&](int s) { return ev.sync(s); };
+  const auto frames_freed = [&](int s) { return ev.sync(n_frame_staging + s); };
+  const auto meta_freed = [&](int s) { return ev.sync(2 * n_frame_staging + s); };
+  const hipEvent_t t_begin = ok && blocking ? ev.timed(0) : nullptr, t_end = ok && blocking ? ev.timed(1) : nullptr;
+  const auto t_group = [&](int lg) { return ev.timed(2 + lg); };
   kvc_status result = ok ? KVC_OK : KVC_ERR_RUNTIME;
 
   // A slot of the frame ring is filled with pieces: runs of consecutive frames of one chunk,
@@ -525,8 +551,8 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
   auto flush = [&]() {
     if (fill.empty() || !ok) return;
     const int fs = (int)(fill_no % n_frame_staging);
-    ok = hipEventRecord(frames_ring.copied[fs], cs) == hipSuccess;  // covers the meta copies before it, too
-    if (ok) ok = hipStreamWaitEvent(xs, frames_ring.copied[fs], 0) == hipSuccess;
+    ok = hipEventRecord(frames_copied(fs), cs) == hipSuccess;  // covers the meta copies before it, too
+    if (ok) ok = hipStreamWaitEvent(xs, frames_copied(fs), 0) == hipSuccess;
     for (size_t k = 0; k < fill.size() && ok; ++k) {
       const Piece& pc = fill[k];
       RestoreParams p = base;
@@ -546,7 +572,7 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
         ok = false;
         break;
       }
-      if (pc.ends_unit) ok = hipEventRecord(meta_ring.freed[pc.meta_slot], xs) == hipSuccess;
+      if (pc.ends_unit) ok = hipEventRecord(meta_freed(pc.meta_slot), xs) == hipSuccess;
       // Layer group lg is complete once the last V frame of the last chunk has been restored
       // (everything else of the group is earlier in both orders).
       if (pc.chunk == n_chunks - 1)
@@ -554,10 +580,10 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
           const int64_t last = ((int64_t)g.LG + lg) * g.F + g.F - 1;
           if (last < pc.first || last >= pc.first + pc.count) continue;
           if (group_ready_events) ok = hipEventRecord(static_cast<hipEvent_t>(group_ready_events[lg]), xs) == hipSuccess;
-          if (ok && group_ready_ms) ok = hipEventRecord(t_group[lg], xs) == hipSuccess;
+          if (ok && group_ready_ms) ok = hipEventRecord(t_group(lg), xs) == hipSuccess;
         }
     }
-    if (ok) ok = hipEventRecord(frames_ring.freed[fs], xs) == hipSuccess;
+    if (ok) ok = hipEventRecord(frames_freed(fs), xs) == hipSuccess;
     fill.clear();
     fill_frames = 0;
     ++fill_no;
@@ -571,7 +597,7 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
     const int ms = (int)(unit_no % n_meta_staging);
     const uint8_t* src = static_cast<const uint8_t*>(chunks[i].host_blob) + meta_off;
     uint8_t* dst = static_cast<uint8_t*>(d_meta_staging[ms]);
-    if (ok && unit_no >= n_meta_staging) ok = hipStreamWaitEvent(cs, meta_ring.freed[ms], 0) == hipSuccess;
+    if (ok && unit_no >= n_meta_staging) ok = hipStreamWaitEvent(cs, meta_freed(ms), 0) == hipSuccess;
     if (lg < 0) {
       if (ok) ok = hipMemcpyAsync(dst, src, meta_bytes, hipMemcpyHostToDevice, cs) == hipSuccess;
     } else {
@@ -595,7 +621,7 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
       const int fs = (int)(fill_no % n_frame_staging);
       if (fill.empty()) {
         fill_first_unit = unit_no;
-        if (fill_no >= n_frame_staging) ok = hipStreamWaitEvent(cs, frames_ring.freed[fs], 0) == hipSuccess;
+        if (fill_no >= n_frame_staging) ok = hipStreamWaitEvent(cs, frames_freed(fs), 0) == hipSuccess;
       }
       const size_t off = (size_t)fill_frames * frame_size;
       if (ok)
@@ -617,7 +643,7 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
     const int fs = (int)(fill_no % n_frame_staging);
     if (fill.empty()) {
       fill_first_unit = unit_no;
-      if (fill_no >= n_frame_staging) ok = hipStreamWaitEvent(cs, frames_ring.freed[fs], 0) == hipSuccess;
+      if (fill_no >= n_frame_staging) ok = hipStreamWaitEvent(cs, frames_freed(fs), 0) == hipSuccess;
     }
     const size_t off = (size_t)fill_frames * frame_size, run = (size_t)g.F * frame_size;
     if (ok)
@@ -656,7 +682,7 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
           result = KVC_ERR_RUNTIME;
         if (group_ready_ms)
           for (int lg = 0; lg < g.LG && result == KVC_OK; ++lg)
-            if (hipEventElapsedTime(&group_ready_ms[lg], t_begin, t_group[lg]) != hipSuccess) result = KVC_ERR_RUNTIME;
+            if (hipEventElapsedTime(&group_ready_ms[lg], t_begin, t_group(lg)) != hipSuccess) result = KVC_ERR_RUNTIME;
       }
     }
     if (result != KVC_OK) {
@@ -664,11 +690,6 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
       (void)hipStreamSynchronize(xs);
     }
   }
-  frames_ring.destroy();
-  meta_ring.destroy();
-  for (hipEvent_t e : t_group) (void)hipEventDestroy(e);
-  if (t_begin) (void)hipEventDestroy(t_begin);
-  if (t_end) (void)hipEventDestroy(t_end);
   return result;
 }
 
@@ -775,21 +796,13 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
     return st;
 
   hipStream_t cs = as_stream(copy_stream), xs = as_stream(compute_stream);
-  // One "copied" event per chunk and one "slot free" event per staging slot.
-  hipEvent_t copied[64], freed[64], t_begin = nullptr, t_end = nullptr;
-  bool ok = true;
-  int n_ev = 0;
-  for (; n_ev < n_staging && ok; ++n_ev) {
-    ok = hipEventCreateWithFlags(&copied[n_ev], hipEventDisableTiming) == hipSuccess;
-    if (ok) {
-      ok = hipEventCreateWithFlags(&freed[n_ev], hipEventDisableTiming) == hipSuccess;
-      if (!ok) (void)hipEventDestroy(copied[n_ev]);
-    }
-    if (!ok) break;
-  }
-  if (ok && fetch_to_ready_ms) {
-    ok = hipEventCreate(&t_begin) == hipSuccess && hipEventCreate(&t_end) == hipSuccess;
-  }
+  // Per staging slot: "copied" after the copy into it, "slot free" after the restore that read it.
+  EventLease ev(2 * n_staging, fetch_to_ready_ms ? 2 : 0);
+  bool ok = ev.ok();
+  const auto copied = [&](int slot) { return ev.sync(slot); };
+  const auto freed = [&](int slot) { return ev.sync(n_staging + slot); };
+  const hipEvent_t t_begin = ok && fetch_to_ready_ms ? ev.timed(0) : nullptr;
+  const hipEvent_t t_end = ok && fetch_to_ready_ms ? ev.timed(1) : nullptr;
   kvc_status result = ok ? KVC_OK : KVC_ERR_RUNTIME;
 
   if (ok) {
@@ -797,10 +810,10 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
     for (int i = 0; i < n_chunks && ok; ++i) {
       const int s = i % n_staging;
       // the copy into slot s must wait for the restore that last read it
-      if (i >= n_staging) ok = hipStreamWaitEvent(cs, freed[s], 0) == hipSuccess;
+      if (i >= n_staging) ok = hipStreamWaitEvent(cs, freed(s), 0) == hipSuccess;
       if (ok) ok = hipMemcpyAsync(d_staging[s], chunks[i].host_blob, blob_bytes, hipMemcpyHostToDevice, cs) == hipSuccess;
-      if (ok) ok = hipEventRecord(copied[s], cs) == hipSuccess;
-      if (ok) ok = hipStreamWaitEvent(xs, copied[s], 0) == hipSuccess;
+      if (ok) ok = hipEventRecord(copied(s), cs) == hipSuccess;
+      if (ok) ok = hipStreamWaitEvent(xs, copied(s), 0) == hipSuccess;
       if (!ok) break;
       RestoreParams p = base;
       p.frames = static_cast<const uint8_t*>(d_staging[s]);
@@ -813,7 +826,7 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
         ok = false;
         break;
       }
-      ok = hipEventRecord(freed[s], xs) == hipSuccess;
+      ok = hipEventRecord(freed(s), xs) == hipSuccess;
     }
     if (!ok && result == KVC_OK) result = KVC_ERR_RUNTIME;
     if (t_end) {
@@ -830,14 +843,6 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
       (void)hipStreamSynchronize(xs);
     }
   }
-  // Destroying an event that is still pending is allowed: its resources are
-  // released once it completes, and the stream-side waits keep their ordering.
-  for (int i = 0; i < n_ev; ++i) {
-    (void)hipEventDestroy(copied[i]);
-    (void)hipEventDestroy(freed[i]);
-  }
-  if (t_begin) (void)hipEventDestroy(t_begin);
-  if (t_end) (void)hipEventDestroy(t_end);
   return result;
 }
 
