@@ -70,9 +70,14 @@ struct PackParams {
   int32_t n_kinds_ch;
   int32_t resident;       // per-channel strips are held in registers (one read of the input)
   int32_t kinds_ch[2];
-  // work units of the two kinds of workgroup and their share per XCD
+  // token positions of the tile rows a token can fall into: chunks of T tokens, and the call's last chunk
+  int32_t positions_full, positions_last;
+  // zero-fill workgroups: planes of layers beyond L, then unused tile rows of full chunks, then of the last chunk
+  uint32_t pieces_plane, pieces_tail_full, pieces_tail_last;
+  uint32_t n_zero_pad, n_zero_full, n_units_zero;
+  // work units of the three kinds of workgroup and their share per XCD
   uint32_t n_units_ch, n_units_tok;
-  uint32_t ch_per_xcd, tok_per_xcd;
+  uint32_t ch_per_xcd, tok_per_xcd, zero_per_xcd;
   uint32_t units_per_xcd;
 };
 

@@ -227,9 +227,8 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
   uint32_t uu = unit;
   const uint32_t tbi = uu % (uint32_t)p.tbc;
   uu /= (uint32_t)p.tbc;
-  const uint32_t l3 = (uint32_t)(3 * g.LG);
-  const uint32_t l = uu % l3;
-  uu /= l3;
+  const uint32_t l = uu % (uint32_t)g.L;
+  uu /= (uint32_t)g.L;
   const uint32_t kind = (uint32_t)p.kinds_tok[uu % (uint32_t)p.n_kinds_tok];
   const uint32_t c = uu / (uint32_t)p.n_kinds_tok;
   if (threadIdx.x >= (uint32_t)(g.apt * p.tpp)) return;  // the block is rounded up to whole waves
@@ -243,10 +242,11 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
 
   const int64_t chunk_first = (int64_t)c * g.T;
   const int64_t left = p.n_tokens - chunk_first;
-  int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
-  if (l >= (uint32_t)g.L) n = 0;  // plane of a layer that does not exist: all zero
+  const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
+  // token positions in the tile rows that can hold a token of this chunk; the rows below are the zero units'
+  const int32_t positions = (int32_t)c + 1 == p.n_chunks ? p.positions_last : p.positions_full;
   const int32_t t0 = (int32_t)tbi * p.tb;
-  const int32_t t1 = t0 + p.tb < g.FG ? t0 + p.tb : g.FG;
+  const int32_t t1 = t0 + p.tb < positions ? t0 + p.tb : positions;
 
   uint32_t r, cc;
   tile_pos(g, e, r, cc);
@@ -305,7 +305,7 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
       uint8_t* dst = code_addr(g, fbase, (uint32_t)t);
       if (t >= n) {  // no token here: zero codes, zero pair
         stream_store<u32x2>(dst, u32x2{0u, 0u});
-        if (leader && t < g.T && l < (uint32_t)g.L) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{0.f, 0.f};
+        if (leader && t < g.T) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{0.f, 0.f};
         continue;
       }
       float lo, hi;
@@ -322,6 +322,11 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
       if (leader) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{q.scale, q.mn};
     }
   }
+  // Pairs of the token positions of this block that the loops did not visit (a short chunk uses fewer tile
+  // rows than a full one; every such position is past the chunk's last token): {0, 0}.
+  const int32_t m1 = t0 + p.tb < g.T ? t0 + p.tb : g.T;
+  for (int32_t t = (t1 > t0 ? t1 : t0) + (int32_t)tsub; t < m1; t += step)
+    if (leader) *reinterpret_cast<f32x2*>(mrow + 2 * (int64_t)t * g.H) = f32x2{0.f, 0.f};
 }
 
 // ---------------------------------------------------------- per-channel groups
@@ -337,9 +342,8 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
   uint32_t uu = unit;
   const uint32_t strip = uu % (uint32_t)p.n_strips;
   uu /= (uint32_t)p.n_strips;
-  const uint32_t l3 = (uint32_t)(3 * g.LG);
-  const uint32_t l = uu % l3;
-  uu /= l3;
+  const uint32_t l = uu % (uint32_t)g.L;
+  uu /= (uint32_t)g.L;
   const uint32_t kind = (uint32_t)p.kinds_ch[uu % (uint32_t)p.n_kinds_ch];
   const uint32_t c = uu / (uint32_t)p.n_kinds_ch;
 
@@ -354,8 +358,8 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
 
   const int64_t chunk_first = (int64_t)c * g.T;
   const int64_t left = p.n_tokens - chunk_first;
-  int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
-  if (l >= (uint32_t)g.L) n = 0;
+  const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
+  const uint32_t positions = (uint32_t)((int32_t)c + 1 == p.n_chunks ? p.positions_last : p.positions_full);
 
   uint32_t r, cc;
   tile_pos(g, e, r, cc);
@@ -427,7 +431,7 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
   }
 
   // pass 2: quantize and scatter; every tile position of the strip is written
-  for (uint32_t tb0 = 0; tb0 < (uint32_t)g.FG; tb0 += U * rows) {
+  for (uint32_t tb0 = 0; tb0 < positions; tb0 += U * rows) {
     u32x4 v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -438,7 +442,7 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t t = tb0 + u * rows + row;
-      if (t >= (uint32_t)g.FG || !active) continue;
+      if (t >= positions || !active) continue;
       u32x2 o{0u, 0u};
       if (t < (uint32_t)n) {
         float x[8];
@@ -466,9 +470,8 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
   uint32_t uu = unit;
   const uint32_t strip = uu % (uint32_t)p.n_strips;
   uu /= (uint32_t)p.n_strips;
-  const uint32_t l3 = (uint32_t)(3 * g.LG);
-  const uint32_t l = uu % l3;
-  uu /= l3;
+  const uint32_t l = uu % (uint32_t)g.L;
+  uu /= (uint32_t)g.L;
   const uint32_t kind = (uint32_t)p.kinds_ch[uu % (uint32_t)p.n_kinds_ch];
   const uint32_t c = uu / (uint32_t)p.n_kinds_ch;
 
@@ -483,8 +486,8 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
 
   const int64_t chunk_first = (int64_t)c * g.T;
   const int64_t left = p.n_tokens - chunk_first;
-  int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
-  if (l >= (uint32_t)g.L) n = 0;
+  const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
+  const uint32_t positions = (uint32_t)((int32_t)c + 1 == p.n_chunks ? p.positions_last : p.positions_full);
 
   uint32_t r, cc;
   tile_pos(g, e, r, cc);
@@ -563,7 +566,7 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const uint32_t t = row + (uint32_t)i * rows;
-    if (t >= (uint32_t)g.FG) continue;
+    if (t >= positions) continue;
     u32x2 o{0u, 0u};
     if (t < (uint32_t)n) {
       float x[8];
@@ -579,12 +582,79 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
     }
     stream_store<u32x2>(fplane + (size_t)off, o);
   }
-  for (uint32_t t = row + (uint32_t)NI * rows; t < (uint32_t)g.FG; t += rows) {
+  for (uint32_t t = row + (uint32_t)NI * rows; t < positions; t += rows) {
     uint32_t gi, f, ty, tx;
     fd_divmod(g.dF, t, gi, f);
     fd_divmod(g.dTX, gi, ty, tx);
     stream_store<u32x2>(fplane + (size_t)(f * frame3 + ty * trs + tx * (uint32_t)g.tw + lane_off), u32x2{0u, 0u});
   }
+}
+
+// ------------------------------------------------------------------ zero fill
+
+// Frame bytes no token of a chunk can reach are cleared by workgroups of their own with plain
+// full-width stores: the planes of layers beyond L, and the tile rows below the last row that
+// holds a token (a chunk shorter than the frame's tile grid, a grid larger than the chunk).
+constexpr uint32_t kZeroPiece = 64u << 10;  // bytes one workgroup clears
+
+// Clears [dst, dst + bytes); dst is 8-byte aligned and bytes a multiple of 8.
+__device__ __forceinline__ void zero_span(uint8_t* dst, uint32_t bytes) {
+  const uint32_t tid = threadIdx.x, nt = blockDim.x;
+  if ((reinterpret_cast<uintptr_t>(dst) & 8u) != 0u && bytes != 0u) {  // one 8-byte store up to 16-byte alignment
+    if (tid == 0) stream_store<u32x2>(dst, u32x2{0u, 0u});
+    dst += 8;
+    bytes -= 8u;
+  }
+  const uint32_t n16 = bytes >> 4;
+  for (uint32_t i = tid; i < n16; i += nt) stream_store<u32x4>(dst + (size_t)i * 16u, u32x4{0u, 0u, 0u, 0u});
+  if ((bytes & 8u) != 0u && tid == 0) stream_store<u32x2>(dst + (size_t)n16 * 16u, u32x2{0u, 0u});
+}
+
+__device__ __forceinline__ void pack_zero_body(const PackParams& p, uint32_t z) {
+  const Geo& g = p.g;
+  const uint32_t F = (uint32_t)g.F, L = (uint32_t)g.L;
+  uint32_t c, kind, l3, f, piece, start;
+  if (z < p.n_zero_pad) {  // plane of a layer that does not exist: all of it
+    piece = z % p.pieces_plane;
+    z /= p.pieces_plane;
+    f = z % F;
+    z /= F;
+    const uint32_t npad = 3u * (uint32_t)g.LG - L;
+    l3 = L + z % npad;
+    z /= npad;
+    kind = z & 1u;
+    c = z >> 1;
+    start = 0u;
+  } else {  // plane of a real layer: the tile rows below the chunk's last used row
+    z -= p.n_zero_pad;
+    uint32_t pieces, positions;
+    if (z < p.n_zero_full) {  // chunks that hold T tokens
+      pieces = p.pieces_tail_full;
+      positions = (uint32_t)p.positions_full;
+      c = 0u;
+    } else {                   // the last chunk of the call, which may be shorter
+      z -= p.n_zero_full;
+      pieces = p.pieces_tail_last;
+      positions = (uint32_t)p.positions_last;
+      c = (uint32_t)p.n_chunks - 1u;
+    }
+    piece = z % pieces;
+    z /= pieces;
+    f = z % F;
+    z /= F;
+    l3 = z % L;
+    z /= L;
+    kind = z & 1u;
+    c += z >> 1;
+    start = positions / ((uint32_t)g.TX * F) * (uint32_t)g.th * (uint32_t)g.W;  // used tile rows * bytes per tile row
+  }
+  const uint32_t plane = (uint32_t)g.plane;
+  const uint64_t lo = (uint64_t)start + (uint64_t)piece * kZeroPiece;
+  if (lo >= plane) return;
+  const uint32_t bytes = plane - (uint32_t)lo < kZeroPiece ? plane - (uint32_t)lo : kZeroPiece;
+  uint8_t* dst = p.frames + (int64_t)c * g.frame_bytes +
+                 ((((int64_t)kind * g.LG + l3 / 3u) * g.F + f) * 3 + l3 % 3u) * g.plane + (int64_t)lo;
+  zero_span(dst, bytes);
 }
 
 template <int DT, bool UNIFORM, bool RESIDENT>
@@ -593,8 +663,9 @@ __global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
   __shared__ float red_lo[kMaxWaves + 1][kMaxStripAtoms * 8];
   __shared__ float red_hi[kMaxWaves + 1][kMaxStripAtoms * 8];
   // Workgroups go to the 8 XCDs round-robin.  Each XCD gets one contiguous range
-  // of the per-channel units and one of the per-token units, so neighbouring
-  // strips and token blocks share an L2 and every XCD has the same mix of work.
+  // of the per-channel units, one of the per-token units and one of the zero-fill
+  // units, so neighbouring strips and token blocks share an L2 and every XCD has
+  // the same mix of work.
   const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
   if (idx < p.ch_per_xcd) {
     const uint32_t unit = xcd * p.ch_per_xcd + idx;
@@ -604,9 +675,12 @@ __global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
       else
         pack_channel_body<DT>(p, unit, red_lo, red_hi);
     }
-  } else {
+  } else if (idx < p.ch_per_xcd + p.tok_per_xcd) {
     const uint32_t unit = xcd * p.tok_per_xcd + (idx - p.ch_per_xcd);
     if (unit < p.n_units_tok) pack_token_body<DT, UNIFORM>(p, unit);
+  } else {
+    const uint32_t unit = xcd * p.zero_per_xcd + (idx - p.ch_per_xcd - p.tok_per_xcd);
+    if (unit < p.n_units_zero) pack_zero_body(p, unit);
   }
 }
 
@@ -641,21 +715,39 @@ kvc_status plan_pack(PackParams& p, int* threads_out) {
   p.tpp = g.apt >= want ? 1 : want / g.apt;
   p.dapt = make_fastdiv((uint32_t)g.apt);
   const int threads = p.resident ? kResidentThreads : (g.apt * p.tpp + 63) / 64 * 64;
+  // Token positions the bodies walk: those of the tile rows a token of the chunk can fall into.  What lies
+  // below is zero and belongs to the zero-fill units, as do the planes of layers beyond L.
+  const auto positions = [&](int64_t n) { return (int32_t)(((n + g.F - 1) / g.F + g.TX - 1) / g.TX * g.TX * g.F); };
+  const int64_t n_last = p.n_tokens - (int64_t)(p.n_chunks - 1) * g.T;
+  p.positions_full = positions(g.T);
+  p.positions_last = positions(n_last);
   p.tb = 256;  // token positions per workgroup of the per-token kinds
-  p.tbc = (g.FG + p.tb - 1) / p.tb;
+  p.tbc = (p.positions_full + p.tb - 1) / p.tb;
   // per-channel part: strips of 8*strip_atoms channels
   p.n_strips = (g.apt + p.strip_atoms - 1) / p.strip_atoms;
   p.rows = threads / p.strip_atoms;
   p.pass_step = p.rows % (g.F * g.TX) == 0 ? (uint32_t)(p.rows / (g.F * g.TX)) * (uint32_t)g.th * (uint32_t)g.W : 0u;
-  const int64_t per_kind = (int64_t)p.n_chunks * 3 * g.LG;
+  const int64_t per_kind = (int64_t)p.n_chunks * g.L;
   const int64_t units_ch = per_kind * p.n_kinds_ch * p.n_strips;
   const int64_t units_tok = per_kind * p.n_kinds_tok * p.tbc;
-  if (units_ch + units_tok > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
+  const auto pieces = [](int64_t bytes) { return (bytes + kZeroPiece - 1) / kZeroPiece; };
+  const int64_t tile_row = (int64_t)g.th * g.W;
+  p.pieces_plane = (uint32_t)pieces(g.plane);
+  p.pieces_tail_full = (uint32_t)pieces(g.plane - p.positions_full / (g.TX * g.F) * tile_row);
+  p.pieces_tail_last = (uint32_t)pieces(g.plane - p.positions_last / (g.TX * g.F) * tile_row);
+  const int64_t zero_pad = (int64_t)p.n_chunks * 2 * (3 * g.LG - g.L) * g.F * p.pieces_plane;
+  const int64_t zero_full = (int64_t)(p.n_chunks - 1) * 2 * g.L * g.F * p.pieces_tail_full;
+  const int64_t zero_last = (int64_t)2 * g.L * g.F * p.pieces_tail_last;
+  if (units_ch + units_tok + zero_pad + zero_full + zero_last > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
   p.n_units_ch = (uint32_t)units_ch;
   p.n_units_tok = (uint32_t)units_tok;
+  p.n_zero_pad = (uint32_t)zero_pad;
+  p.n_zero_full = (uint32_t)zero_full;
+  p.n_units_zero = (uint32_t)(zero_pad + zero_full + zero_last);
   p.ch_per_xcd = (p.n_units_ch + 7u) / 8u;
   p.tok_per_xcd = (p.n_units_tok + 7u) / 8u;
-  p.units_per_xcd = p.ch_per_xcd + p.tok_per_xcd;
+  p.zero_per_xcd = (p.n_units_zero + 7u) / 8u;
+  p.units_per_xcd = p.ch_per_xcd + p.tok_per_xcd + p.zero_per_xcd;
   *threads_out = threads;
   return KVC_OK;
 }
