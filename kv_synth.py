@@ -62,6 +62,10 @@ WORKLOADS = {
     "llama3_8b_32k_paged": Workload("llama3_8b_32k_paged", 2, L=32, H=8, D=128, n_tokens=32768, dtype="f16", paged=True),
     "yi34b_80k_paged": Workload("yi34b_80k_paged", 3, L=60, H=8, D=128, n_tokens=80000, dtype="bf16", paged=True),
     "llama3_8b_32k_pipeline": Workload("llama3_8b_32k_pipeline", 4, L=32, H=8, D=128, n_tokens=32768, dtype="f16", paged=True),
+    # not one of the benchmark configurations: the paper's own chunking (Sec. 4 item (1): 10K-token chunks) on a
+    # 1080P frame, 1920 x 1080 pixels = 15 x 135 tiles of (8,128), F = 6; three chunks
+    "llama3_8b_30k_chunk10k": Workload("llama3_8b_30k_chunk10k", 5, L=32, H=8, D=128, n_tokens=30720, dtype="f16",
+                                       T=10240, TX=15, TY=135, paged=True),
 }
 
 
