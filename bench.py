@@ -133,20 +133,34 @@ def main():
     roof_rest = roof("restore_kernel (kvc_restore_paged)", restore_bytes, rest_avg, rest_ms)
     dominant, other = (roof_pack, roof_rest) if pack_avg >= rest_avg else (roof_rest, roof_pack)
 
-    # a plain device copy (torch's copy_ kernel) of a third of the restore bytes: a familiar reference point, not a
-    # ceiling -- one-shot copy kernels of this repo's probes run 20-30 % faster (profiles/hbm_microbenchmarks.txt)
-    a = torch.empty(restore_bytes // 3, dtype=torch.uint8, device=dev)
-    b = torch.empty_like(a)
-    for _ in range(2):
-        b.copy_(a)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(5):
-        b.copy_(a)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    copy_gbps = 2 * a.numel() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del a, b
+    # Reference copies with the byte ratio of restore (1 byte read, 2 written per element), 4 GiB of output:
+    # sequential, and with the output cut into 32 KB pieces (one block of this workload's paged cache) that land
+    # in seeded random order inside 64 MB windows (one (layer, kind) region of the cache), each in one-shot
+    # workgroups of 4 KB and of 32 KB.  They show what the part delivers for the pattern restore is asked for.
+    ref_out = 1 << 32
+    src_ref = torch.empty(ref_out // 2, dtype=torch.uint8, device=dev)
+    dst_ref = torch.empty(ref_out, dtype=torch.uint8, device=dev)
+    piece, window = 32768, 64 << 20
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(w.seed)
+    per_win = window // piece
+    pmap = torch.cat([torch.randperm(per_win, generator=gen) + i * per_win for i in range(ref_out // window)])
+    pmap = pmap.to(torch.int32).to(dev)
+    hbm_reference = {}
+    for name, mp, wg in (("expand_sequential_wg4K", 0, 4096), ("expand_sequential_wg32K", 0, 32768),
+                         ("expand_random_32K_pieces_wg4K", pmap.data_ptr(), 4096),
+                         ("expand_random_32K_pieces_wg32K", pmap.data_ptr(), 32768)):
+        best = None
+        for it in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            kvc.kvc_probe_expand(src_ref.data_ptr(), dst_ref.data_ptr(), ref_out, mp, piece, wg, sh)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            if it:
+                best = min(best or 1e9, e0.elapsed_time(e1))
+        hbm_reference[name] = round(1.5 * ref_out / (best * 1e-3) / 1e9, 1)
+    del src_ref, dst_ref, pmap
 
     # the same restore with physical blocks in logical order: what the seeded random placement of the workload costs
     seq_table = torch.arange(n_logical, dtype=torch.int32, device=dev)
@@ -179,7 +193,7 @@ def main():
         "restore_sequential_blocks": {"avg_ms": round(seq_avg, 4),
                                       "achieved": round(restore_bytes / (seq_avg * 1e-3) / 1e9, 1),
                                       "frac": round(restore_bytes / (seq_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
-        "device_copy_GBps": round(copy_gbps, 1),
+        "hbm_reference_GBps": hbm_reference,
         "build_id": kvc.build_id(),
     }
 

@@ -418,6 +418,23 @@ double kvc_proxy_cost_bits(const kvc_layout* layout, const uint64_t* hist, int64
 int32_t kvc_tile_candidates(int32_t num_kv_heads, int32_t head_dim, int32_t* tile_h, int32_t* tile_w,
                             int32_t* tile_seg, int32_t cap);
 
+/* Measurement aid, not a step of the paper's path: a streaming copy with the byte
+ * ratio of restore (8 bytes read and 16 written per lane).  The benchmark runs it
+ * to show what the part delivers for sequential output and for output cut into
+ * pieces that land in a given order, and as the copy of known size that profiler
+ * byte counters are scaled by.
+ *   d_src        DEVICE in : out_bytes / 2 bytes, 8-byte aligned
+ *   d_dst        DEVICE out: out_bytes bytes, 16-byte aligned; every byte written
+ *                when the map is a permutation
+ *   d_piece_map  DEVICE in, may be NULL: piece i of the output (piece_bytes each,
+ *                in source order) is written at piece position d_piece_map[i];
+ *                entries must be < out_bytes / piece_bytes (not checked: they
+ *                are device memory).  NULL: sequential output.
+ *   piece_bytes  a power of two, 32768 .. 2^30, dividing out_bytes
+ *   wg_bytes     output bytes one workgroup moves in one shot: 4096 or 32768 */
+kvc_status kvc_probe_expand(const void* d_src, void* d_dst, size_t out_bytes, const uint32_t* d_piece_map,
+                            size_t piece_bytes, int32_t wg_bytes, void* stream);
+
 const char* kvc_status_str(kvc_status status);
 
 /* Identifier of what this binary was built from: a hash of the library's

@@ -144,14 +144,20 @@ def make_kv_correlated(L, H, D, n_tokens, dtype, seed, device="cpu", rho=0.8, me
     g = torch.sign(_smooth_along_dim(randn(L, 2, H, D), 16))
     g = torch.where(g == 0, torch.ones_like(g), g)
     kv = torch.empty((L, 2, n_tokens, H, D), dtype=dtype, device=device)
-    innov = math.sqrt(1.0 - rho * rho)
-    a = randn(L, 2, H, 1)
-    e = randn(L, 2, H, D)
     sa, se = math.sqrt(head_share), math.sqrt(1.0 - head_share)
     sig = sigma.view(L, 2, H, D)
-    for t in range(n_tokens):
-        if t:
-            a = rho * a + innov * randn(L, 2, H, 1)
-            e = rho * e + innov * randn(L, 2, H, D)
-        kv[:, :, t] = (sig * (m + sa * g * a + se * e)).to(dtype)
+    # AR(1) in blocks of B tokens: x[t0 + k] = rho^(k+1) x[t0 - 1] + sum_{j <= k} rho^(k-j) * innov * z[t0 + j], i.e. one
+    # lower-triangular Toeplitz product per block instead of one step per token
+    B = 64
+    k = torch.arange(B, device=device, dtype=torch.float32)
+    tri = torch.tril(rho ** (k[:, None] - k[None, :]).clamp(min=0)) * math.sqrt(1.0 - rho * rho)   # [B][B]
+    carry = (rho ** (k + 1)).view(B, 1, 1, 1, 1)
+    a_prev = randn(L, 2, H, 1)       # state before the first token: a draw from the stationary distribution
+    e_prev = randn(L, 2, H, D)
+    for t0 in range(0, n_tokens, B):
+        nb = min(B, n_tokens - t0)
+        a = carry[:nb] * a_prev + torch.einsum("kj,jlchd->klchd", tri[:nb, :nb], randn(nb, L, 2, H, 1))
+        e = carry[:nb] * e_prev + torch.einsum("kj,jlchd->klchd", tri[:nb, :nb], randn(nb, L, 2, H, D))
+        a_prev, e_prev = a[-1], e[-1]
+        kv[:, :, t0:t0 + nb] = (sig * (m + sa * g * a + se * e)).to(dtype).permute(1, 2, 0, 3, 4)
     return kv

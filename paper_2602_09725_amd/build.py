@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvc.so")
-SOURCES = ["kvc_api.hip", "kvc_restore.hip", "kvc_pack.hip", "kvc_score.hip"]
+SOURCES = ["kvc_api.hip", "kvc_restore.hip", "kvc_pack.hip", "kvc_score.hip", "kvc_probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -56,7 +56,7 @@ def is_current(lib=LIB):
 def build(out=LIB, extra_flags=()):
     cmd = ["hipcc", *FLAGS, *extra_flags, f'-DKVC_BUILD_ID="{source_id(extra_flags)}"',
            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", out]
-    cmd += [os.path.join(CSRC, s) for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    cmd += [os.path.join(CSRC, s) for s in SOURCES]
     subprocess.run(cmd, check=True)
     return out
 

@@ -339,6 +339,19 @@ int32_t kvc_tile_candidates(int32_t num_kv_heads, int32_t head_dim, int32_t* til
   return n;
 }
 
+kvc_status kvc_probe_expand(const void* d_src, void* d_dst, size_t out_bytes, const uint32_t* d_piece_map,
+                            size_t piece_bytes, int32_t wg_bytes, void* stream) {
+  if (wg_bytes != 4096 && wg_bytes != 32768) return KVC_ERR_INVALID_ARG;
+  if (piece_bytes < 32768 || (piece_bytes & (piece_bytes - 1)) != 0 || piece_bytes > ((size_t)1 << 30)) return KVC_ERR_INVALID_ARG;
+  if (out_bytes % piece_bytes != 0 || out_bytes / piece_bytes > 0xffffffffull) return KVC_ERR_INVALID_ARG;
+  if (out_bytes == 0) return KVC_OK;
+  if (!d_src || !d_dst || !aligned(d_src, 8) || !aligned(d_dst, 16) || (d_piece_map && !aligned(d_piece_map, 4)))
+    return KVC_ERR_INVALID_ARG;
+  uint32_t log2_piece = 0;
+  while (((size_t)1 << log2_piece) < piece_bytes) ++log2_piece;
+  return launch_probe_expand(d_src, d_dst, out_bytes, d_piece_map, log2_piece, wg_bytes, as_stream(stream));
+}
+
 size_t kvc_frame_size(const kvc_layout* layout) {
   Geo g;
   if (make_geo(layout, &g) != KVC_OK) return (size_t)-1;

@@ -1,0 +1,55 @@
+// Reference streaming kernel for the measurements (not a step of the paper's path): a copy with the
+// byte ratio of restore -- 8 bytes read and 16 written per lane, i.e. 1 byte in for 2 bytes out -- whose
+// destination can be cut into pieces that land in a caller-given order.  bench.py runs it sequentially
+// and with 32 KB pieces (one cache block of the paged workload) in seeded random order, in one-shot
+// workgroups of 4 KB and of 32 KB, to show what the part delivers for the access pattern the restore
+// kernel is asked for, and uses its sequential form as the copy of known size that the rocprofv3
+// FETCH_SIZE / WRITE_SIZE counters are scaled by.
+#include <hip/hip_runtime.h>
+
+#include "kvc_device.h"
+#include "kvc_launch.h"
+
+namespace kvc {
+
+namespace {
+
+// A workgroup moves THREADS * U * 16 bytes of output in one shot: all loads, then all stores.
+template <int THREADS, int U>
+__global__ void __launch_bounds__(THREADS) expand_kernel(const u32x2* __restrict__ src, u32x4* __restrict__ dst,
+                                                         const uint32_t* __restrict__ piece_map, uint32_t log2_vec_per_piece) {
+  const size_t base = (size_t)blockIdx.x * THREADS * U;
+  const uint32_t t = threadIdx.x;
+  u32x2 v[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) v[u] = stream_load<u32x2>(src + base + (size_t)u * THREADS + t);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const size_t j = base + (size_t)u * THREADS + t;  // 16-byte vector of the output, in source order
+    size_t d = j;
+    if (piece_map) {
+      const size_t piece = j >> log2_vec_per_piece, off = j & (((size_t)1 << log2_vec_per_piece) - 1);
+      d = ((size_t)piece_map[piece] << log2_vec_per_piece) + off;
+    }
+    stream_store<u32x4>(dst + d, u32x4{v[u].x, v[u].y, v[u].x ^ v[u].y, (uint32_t)j});
+  }
+}
+
+}  // namespace
+
+kvc_status launch_probe_expand(const void* src, void* dst, size_t out_bytes, const uint32_t* piece_map, uint32_t log2_piece,
+                               int32_t wg_bytes, hipStream_t stream) {
+  const uint32_t lg = log2_piece - 4;  // 16-byte vectors per piece
+  const size_t wgs = out_bytes / (size_t)wg_bytes;
+  if (wgs == 0) return KVC_OK;
+  if (wgs > 0x7fffffff) return KVC_ERR_UNSUPPORTED;
+  if (wg_bytes == 4096)
+    hipLaunchKernelGGL((expand_kernel<256, 1>), dim3((uint32_t)wgs), dim3(256), 0, stream, static_cast<const u32x2*>(src),
+                       static_cast<u32x4*>(dst), piece_map, lg);
+  else
+    hipLaunchKernelGGL((expand_kernel<512, 4>), dim3((uint32_t)wgs), dim3(512), 0, stream, static_cast<const u32x2*>(src),
+                       static_cast<u32x4*>(dst), piece_map, lg);
+  return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_RUNTIME;
+}
+
+}  // namespace kvc

@@ -102,6 +102,7 @@ def load(path=None):
     ip = C.POINTER(i32)
     lib.kvc_tile_candidates.argtypes = [i32, i32, ip, ip, ip, i32]
     lib.kvc_tile_candidates.restype = i32
+    lib.kvc_probe_expand.argtypes = [vp, vp, sz, vp, sz, i32, vp]
     if path is None:
         _lib = lib
     return lib
@@ -157,6 +158,11 @@ def kvc_restore_paged(layout, frames_ptr, meta_ptr, first_token, n_tokens, layer
     _check(load().kvc_restore_paged(C.byref(layout), frames_ptr, meta_ptr, first_token, n_tokens,
                                     layer_cache_ptrs_dev, num_blocks, block_size, block_table_ptr, table_len, err_ptr,
                                     stream), "kvc_restore_paged")
+
+
+def kvc_probe_expand(src_ptr, dst_ptr, out_bytes, piece_map_ptr, piece_bytes, wg_bytes, stream=0):
+    _check(load().kvc_probe_expand(src_ptr, dst_ptr, out_bytes, piece_map_ptr, piece_bytes, wg_bytes, stream),
+           "kvc_probe_expand")
 
 
 N_RESIDUALS = 5

@@ -696,3 +696,27 @@ def test_config_frame_pipeline_matches_chunk_restore():
             assert torch.equal(cache.layers[l], ref.layers[l]), f"graph replay {rep}: layer {l}"
     # the cache the last replay filled, chunk by chunk and layer by layer against the oracle
     oracle_check_cache(w, olo, blobs, fb, moff, mb, table.cpu().numpy(), cache, "frame pipeline (graph replay)")
+
+
+@pytest.mark.parametrize("wg", [4096, 32768])
+def test_reference_expand_copy_moves_every_vector_where_the_map_says(wg):
+    """The measurement aid kvc_probe_expand: vector j of the source order lands in piece map[j / per_piece] at the
+    same offset, with and without a map; nothing outside the destination is written."""
+    out_bytes, piece = 3 << 20, 32768
+    n_vec, per_piece = out_bytes // 16, piece // 16
+    src = torch.randint(-2**31, 2**31 - 1, (n_vec, 2), dtype=torch.int32, device="cuda")
+    guard = 1024
+    for use_map in (False, True):
+        buf = torch.full((guard + n_vec * 4 + guard,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+        dst = buf[guard:guard + n_vec * 4]
+        assert dst.data_ptr() % 16 == 0
+        pm = torch.randperm(out_bytes // piece, generator=torch.Generator().manual_seed(3)).to(torch.int32).cuda()
+        hz.kvc.kvc_probe_expand(src.data_ptr(), dst.data_ptr(), out_bytes, pm.data_ptr() if use_map else 0, piece, wg,
+                                hz.stream_handle())
+        torch.cuda.synchronize()
+        j = torch.arange(n_vec, device="cuda")
+        want = torch.stack([src[:, 0], src[:, 1], src[:, 0] ^ src[:, 1], j.to(torch.int32)], dim=1)
+        where = (pm.long()[j // per_piece] * per_piece + j % per_piece) if use_map else j
+        got = dst.view(n_vec, 4)[where]
+        assert torch.equal(got, want)
+        assert bool((buf[:guard] == 0x5A5A5A5A).all()) and bool((buf[guard + n_vec * 4:] == 0x5A5A5A5A).all())

@@ -340,3 +340,16 @@ def test_residual_histograms_reject_bad_arguments(kvc_lib):
             kvc.kvc_residual_histograms(lo, *args)
         assert e.value.status == status
     kvc.kvc_residual_histograms(lo, A, 0, A, 0)   # nothing to do: returns before anything is enqueued
+
+
+def test_probe_expand_rejects_bad_arguments(kvc_lib):
+    A = 0x7F0000000000
+    ok = dict(out=1 << 20, mp=0, piece=32768, wg=4096)
+    for kw, status in ((dict(wg=8192), 1), (dict(piece=4096), 1), (dict(piece=48 * 1024), 1), (dict(out=(1 << 20) + 4096), 1),
+                       (dict(src=0), 1), (dict(dst=A + 8), 1), (dict(mp=A + 2), 1)):
+        a = dict(ok, src=A, dst=A)
+        a.update(kw)
+        with pytest.raises(kvc.KvcError) as e:
+            kvc.kvc_probe_expand(a["src"], a["dst"], a["out"], a["mp"], a["piece"], a["wg"])
+        assert e.value.status == status, kw
+    kvc.kvc_probe_expand(A, A, 0, 0, 32768, 4096)   # nothing to do
