@@ -95,7 +95,6 @@ struct ScoreParams {
   int32_t n_chunks;
   uint64_t* hist;         // [n_chunks][2][L][KVC_N_RESIDUALS][256]
   FastDiv dL;             // stream -> (chunk, kind), layer
-  FastDiv dper_row;       // 8-pixel pieces per plane row
 };
 
 // Enqueues the residual-histogram kernel of the tiling proxy: one workgroup per (chunk, kind, layer).

@@ -9,7 +9,8 @@
 //
 // One workgroup per plane sequence (chunk, kind, layer): it owns the five histograms of its stream,
 // so the result needs no atomics in global memory and no cleared buffer.  Every frame byte is read
-// from HBM once; the row above and the byte to the left come from cache.  Counting is done with LDS
+// from HBM once: a thread walks down a column, so the row above is its own previous read (a cache hit),
+// and the byte to the left sits in the line it is reading anyway.  Counting is done with LDS
 // atomics on 16 copies of the histograms (lanes spread over the copies, so that equal residuals in one
 // wave seldom meet in one counter), which is what bounds the kernel: five counter updates per pixel
 // against one byte of HBM traffic; with the counting switched off the same loop runs in a third of the time.
@@ -63,11 +64,22 @@ __global__ void __launch_bounds__(kScoreThreads) residual_hist_kernel(const Scor
   const uint32_t lg = l / 3u, pl = l - lg * 3u;
   const uint8_t* base = p.frames + (int64_t)c * g.frame_bytes + (((int64_t)kind * g.LG + lg) * g.F * 3 + pl) * g.plane;
   const int64_t frame_stride = 3 * g.plane;
-  const uint32_t W = (uint32_t)g.W, per_row = W / 8u, n_pieces = (uint32_t)(g.plane / 8);
+  const uint32_t W = (uint32_t)g.W, per_row = W / 8u;
   const uint32_t copy = tid & (kCopies - 1);
 
-  for (uint32_t q = tid; q < n_pieces; q += kScoreThreads) {  // piece = 8 pixels of a row; rows are contiguous
-    const uint32_t y = fd_div(p.dper_row, q);
+  // A thread walks down a column of 8-pixel pieces, so the row above is what it read itself one step earlier (a
+  // cache hit, never a second miss in flight for the same line).  Rows narrower than the workgroup are cut into
+  // bands of rows worked side by side; wider rows are taken in blocks of kScoreThreads columns.
+  const uint32_t cols = per_row < (uint32_t)kScoreThreads ? per_row : (uint32_t)kScoreThreads;
+  const uint32_t bands = (uint32_t)kScoreThreads / cols;
+  const uint32_t band = tid / cols, col0 = tid - band * cols;
+  const uint32_t rows_per_band = ((uint32_t)g.Hp + bands - 1u) / bands;
+  const uint32_t y0 = band * rows_per_band;
+  uint32_t y1 = y0 + rows_per_band;
+  y1 = y1 < (uint32_t)g.Hp ? y1 : (uint32_t)g.Hp;
+  for (uint32_t cb = col0; band < bands && cb < per_row; cb += cols)
+  for (uint32_t y = y0; y < y1; ++y) {
+    const uint32_t q = y * per_row + cb;  // piece = 8 pixels of a row; rows are contiguous
     const bool has_up = y > 0u, has_left = q - y * per_row > 0u;
     u32x2 prev{0u, 0u}, prev_up{0u, 0u};
     uint32_t prev_left = 0u;
@@ -110,7 +122,6 @@ kvc_status launch_residual_histograms(ScoreParams p, hipStream_t stream) {
   const int64_t streams = (int64_t)p.n_chunks * 2 * g.L;
   if (streams > 0x7fffffff) return KVC_ERR_UNSUPPORTED;
   p.dL = make_fastdiv((uint32_t)g.L);
-  p.dper_row = make_fastdiv((uint32_t)(g.W / 8));
   hipLaunchKernelGGL(residual_hist_kernel, dim3((uint32_t)streams), dim3(kScoreThreads), 0, stream, p);
   return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_RUNTIME;
 }
