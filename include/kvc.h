@@ -188,7 +188,7 @@ kvc_status kvc_restore(const kvc_layout* layout, const uint8_t* frames, const vo
  * straight to slots the engine has already allocated in its paged memory;
  * Sec. 4 item (2): the sparse frame-to-paged-memory transfer operator).
  *   frames, meta   DEVICE in : sections of the chunks that hold sequence
- *                  positions [first_token, first_token + n_tokens).  `frames`
+ *                  positions [first_token, first_token + n_tokens).  Either
  *                  may also be pinned host memory that is mapped into the
  *                  device (hipHostMalloc): the kernel then reads it over the
  *                  host link and no staging copy is needed.

@@ -584,6 +584,14 @@ def test_restore_reads_frames_from_mapped_pinned_host_memory():
     hz.gpu_restore_paged(glo, host, meta, 0, n, got, tab)
     for l in range(L):
         assert torch.equal(got.layers[l], ref.layers[l])
+    # the pairs from pinned host memory as well
+    host_meta = torch.empty(meta.numel(), dtype=torch.float32, pin_memory=True)
+    host_meta.copy_(meta)
+    torch.cuda.synchronize()
+    got2 = hz.PagedCache(L, n_logical + 2, bs, H * D)
+    hz.gpu_restore_paged(glo, host, host_meta, 0, n, got2, tab)
+    for l in range(L):
+        assert torch.equal(got2.layers[l], ref.layers[l])
 
 
 def test_frame_restore_bad_block_ids():
