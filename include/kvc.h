@@ -168,10 +168,11 @@ kvc_status kvc_pack(const kvc_layout* layout, const void* kv, kvc_strides stride
  * only, nothing is enqueued (Sec. 4 item (1), the offline compression pass).
  *   *resident  HOST out, nullable: 1 when the strip of channels a workgroup
  *              quantizes per channel is held in registers for a whole chunk, so
- *              the input is read from memory once; 0 when the strip is streamed
- *              twice (chunk_tokens > 2048, or 2048 * token_stride * 2 bytes does
- *              not fit the 32-bit offsets of the register-resident body) or no
- *              kind is quantized per channel
+ *              the input is read from memory once; 0 when only the last 3072
+ *              tokens of a chunk's strip wait on chip and the tokens before them
+ *              are read twice (chunk_tokens > 2048, or 2048 * token_stride * 2
+ *              bytes does not fit the 32-bit offsets of the register-resident
+ *              body), or when no kind is quantized per channel
  *   *threads   HOST out, nullable: threads per workgroup of the launch
  * Returns the status kvc_pack would return for the same layout and strides. */
 kvc_status kvc_pack_plan(const kvc_layout* layout, kvc_strides strides, int32_t* resident, int32_t* threads);

@@ -9,25 +9,31 @@
 //    min/max with a cross-lane butterfly, so the input is read exactly once.
 //  * per-channel groups (one group = one channel over the valid tokens of a
 //    chunk): a workgroup owns a strip of channels of one (chunk, kind, layer).
-//    A chunk of up to 2048 tokens is loaded once into the registers of a
-//    1024-thread workgroup, reduced to the column min/max (registers + one LDS
-//    step across waves) and quantized from the registers; longer chunks stream
-//    the strip twice (statistics, then quantization).
+//    A chunk of up to 2048 tokens is loaded once into the registers and the
+//    LDS of a 512-thread workgroup that has its CU to itself, reduced to the
+//    column min/max (registers + one LDS step across waves) and quantized from
+//    where it waits; of longer chunks the last 3072 tokens wait like that and
+//    the tokens before them are read twice (statistics, then quantization).
 // Both kernels write every byte of their part of the frame section, zero for
 // tile positions without a token and for the planes of layers beyond L, so the
 // caller never has to clear the buffer.
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 
 #include "kvc_device.h"
 #include "kvc_launch.h"
 
 namespace kvc {
 
+#ifndef KVC_PACK_U_RESIDENT
+#define KVC_PACK_U_RESIDENT 8  // loads in flight per thread of the per-token body beside the resident strips (8 waves per CU)
+#endif
 #ifndef KVC_PACK_U
-#define KVC_PACK_U 4  // loads in flight per thread
+#define KVC_PACK_U 4  // ... beside the streamed strips (16 waves per CU)
 #endif
 #ifndef KVC_PACK_STREAM_U
-#define KVC_PACK_STREAM_U 8  // ... of the two-pass per-channel body
+#define KVC_PACK_STREAM_U 4  // ... of the two-pass per-channel body (next to the 16 it keeps)
 #endif
 #ifndef KVC_PACK_STREAM_ATOMS
 #define KVC_PACK_STREAM_ATOMS 8  // atoms per strip of the two-pass per-channel body
@@ -226,9 +232,8 @@ __device__ __forceinline__ void head_minmax16(float& lo, float& hi) {
   hi = __builtin_fmaxf(hi, dpp_move<0x140>(hi));
 }
 
-template <int DT, bool UNIFORM>
+template <int DT, bool UNIFORM, int U>
 __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t unit) {
-  constexpr int U = KVC_PACK_U;
   const Geo& g = p.g;
   uint32_t uu = unit;
   const uint32_t tbi = uu % (uint32_t)p.tbc;
@@ -337,13 +342,21 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
 
 // ---------------------------------------------------------- per-channel groups
 
-constexpr int kMaxWaves = 16;       // 1024 threads
 constexpr int kMaxStripAtoms = 16;  // 128 channels
+
+// Streaming variant for chunks too long for the register-resident strip: the strip is read twice, once for the
+// column statistics and once to quantize -- except its last (kStreamTailLoads + kStreamStashLoads) * rows tokens
+// (3072 with 1024 threads), which wait on chip between the two passes: 16 loads per thread in registers, 8 more in the
+// CU's LDS (128 KB of its 160 KB; the workgroup has the CU to itself anyway).  Every thread reads back the LDS words it wrote itself, so the stash needs no barrier.
+constexpr int kStreamTailLoads = 16;
+constexpr int kStreamStashLoads = 8;
 
 template <int DT>
 __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t unit, float (*red_lo)[kMaxStripAtoms * 8],
-                                                  float (*red_hi)[kMaxStripAtoms * 8]) {
+                                                  float (*red_hi)[kMaxStripAtoms * 8], u32x4* stash) {
   constexpr int U = KVC_PACK_STREAM_U;
+  constexpr int NT = kStreamTailLoads, NS = kStreamStashLoads;
+  static_assert(NS % U == 0, "the stash is filled in steps of U loads");
   const Geo& g = p.g;
   uint32_t uu = unit;
   const uint32_t strip = uu % (uint32_t)p.n_strips;
@@ -364,8 +377,12 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
 
   const int64_t chunk_first = (int64_t)c * g.T;
   const int64_t left = p.n_tokens - chunk_first;
-  const int32_t n = left < (int64_t)g.T ? (int32_t)left : g.T;
+  const uint32_t n = left < (int64_t)g.T ? (uint32_t)left : (uint32_t)g.T;
   const uint32_t positions = (uint32_t)((int32_t)c + 1 == p.n_chunks ? p.positions_last : p.positions_full);
+  // tokens [0, head_n) are streamed twice; [head_n, tail_0) wait in LDS and [tail_0, n) in registers
+  const uint32_t head_n = n > (uint32_t)(NT + NS) * rows ? n - (uint32_t)(NT + NS) * rows : 0u;
+  const uint32_t tail_0 = head_n + (uint32_t)NS * rows;
+  u32x4* const mine = stash + tid;  // slot i of this thread: mine[i * blockDim.x]
 
   uint32_t r, cc;
   tile_pos(g, e, r, cc);
@@ -380,22 +397,44 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
     mnv[i] = 0.f;
     inv[i] = 0.f;
   }
+  u32x4 tail[NT];
 
   if (n > 0) {
     // pass 1: column min / max of the strip over the chunk's valid tokens
     ColumnStats<DT> st;
     st.init();
-    for (uint32_t tb0 = 0; tb0 < (uint32_t)n; tb0 += U * rows) {
+    for (uint32_t tb0 = 0; tb0 < head_n; tb0 += U * rows) {
       u32x4 v[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t t = tb0 + u * rows + row;
-        const uint32_t tc = t < (uint32_t)n ? t : (uint32_t)n - 1u;  // a repeated token leaves min / max unchanged
+        const uint32_t tc = t < head_n ? t : head_n - 1u;  // a repeated token leaves min / max unchanged
         v[u] = *reinterpret_cast<const u32x4*>(src + (int64_t)tc * p.ts);  // cached: read again in pass 2
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) st.add(v[u]);
     }
+#pragma unroll
+    for (int i0 = 0; i0 < NS; i0 += U) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t t = head_n + (uint32_t)(i0 + u) * rows + row;
+        v[u] = stream_load<u32x4>(src + (int64_t)(t < n ? t : n - 1u) * p.ts);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        st.add(v[u]);
+        mine[(uint32_t)(i0 + u) * blockDim.x] = v[u];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+      const uint32_t t = tail_0 + (uint32_t)i * rows + row;
+      tail[i] = stream_load<u32x4>(src + (int64_t)(t < n ? t : n - 1u) * p.ts);
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i) st.add(tail[i]);
     // lanes holding the same atom differ by multiples of sa
     for (uint32_t m = sa; m < 64u; m <<= 1) st.merge_xor((int)m);
     float lo[8], hi[8];
@@ -411,8 +450,8 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
     }
     __syncthreads();
     // one thread per channel of the strip finishes the reduction and derives the group's parameters
-    float* par_mn = &red_lo[kMaxWaves][0];
-    float* par_inv = &red_hi[kMaxWaves][0];
+    float* par_mn = &red_lo[n_waves][0];
+    float* par_inv = &red_hi[n_waves][0];
     if (tid < sa * 8u) {
       float l0 = red_lo[0][tid], h0 = red_hi[0][tid];
       for (uint32_t w = 1; w < n_waves; ++w) {
@@ -435,43 +474,67 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
       inv[i] = par_inv[a * 8 + i];
     }
   }
+  if (!active) return;  // after the barriers: lanes of a ragged last strip store nothing
 
-  // pass 2: quantize and scatter; every tile position of the strip is written
-  for (uint32_t tb0 = 0; tb0 < positions; tb0 += U * rows) {
+  // pass 2: quantize and scatter -- the streamed tokens from memory again, ...
+  for (uint32_t tb0 = 0; tb0 < head_n; tb0 += U * rows) {
     u32x4 v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t t = tb0 + u * rows + row;
       v[u] = u32x4{0u, 0u, 0u, 0u};
-      if (t < (uint32_t)n) v[u] = stream_load<u32x4>(src + (int64_t)t * p.ts);
+      if (t < head_n) v[u] = stream_load<u32x4>(src + (int64_t)t * p.ts);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t t = tb0 + u * rows + row;
-      if (t >= positions || !active) continue;
-      u32x2 o{0u, 0u};
-      if (t < (uint32_t)n) {
-        float x[8];
-        widen_atom<DT>(v[u], x);
-        o = quantize_atom(x, mnv, inv);
-      }
-      stream_store<u32x2>(code_addr(g, fbase, t), o);
+      if (t >= head_n) continue;
+      float x[8];
+      widen_atom<DT>(v[u], x);
+      stream_store<u32x2>(code_addr(g, fbase, t), quantize_atom(x, mnv, inv));
     }
   }
+  // ... the kept tokens from LDS and from the registers, ...
+#pragma unroll
+  for (int i = 0; i < NS; ++i) {
+    const uint32_t t = head_n + (uint32_t)i * rows + row;
+    if (t >= n) continue;
+    float x[8];
+    widen_atom<DT>(mine[(uint32_t)i * blockDim.x], x);
+    stream_store<u32x2>(code_addr(g, fbase, t), quantize_atom(x, mnv, inv));
+  }
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const uint32_t t = tail_0 + (uint32_t)i * rows + row;
+    if (t >= n) continue;
+    float x[8];
+    widen_atom<DT>(tail[i], x);
+    stream_store<u32x2>(code_addr(g, fbase, t), quantize_atom(x, mnv, inv));
+  }
+  // ... and zeros for the tile positions of the used tile rows that hold no token.
+  for (uint32_t t = n + row; t < positions; t += rows) stream_store<u32x2>(code_addr(g, fbase, t), u32x2{0u, 0u});
 }
 
-// Register-resident variant: the strip of one (chunk, kind, layer) -- up to
-// kResidentLoads * rows tokens x 64 channels, 256 KB of fp16 at 1024 threads --
-// is loaded once into VGPRs (64 per thread), reduced, and quantized from the
-// registers, so the input is read from HBM exactly once.  The CDNA register file
-// (512 KB per CU) is what makes this possible; LDS (160 KB) could not hold it.
-constexpr int kResidentLoads = 16;
+// Resident variant: the strip of one (chunk, kind, layer) -- up to kResidentLoads * rows tokens x 128
+// channels, 512 KB of fp16 at 512 threads -- is loaded once, reduced, and quantized from where it waits, so
+// the input is read from HBM exactly once.  Of a thread's 64 loads 46 wait in its registers (184 VGPRs of the
+// 256 a wave gets at two waves per SIMD) and 18 in LDS (144 KB of the CU's 160 KB), each thread reading back
+// the words it wrote itself, so the LDS part needs no barrier.  A strip as wide as a 128-byte line of codes is
+// what this buys: strips of 64 channels, which fit the registers alone, share every code line with their
+// neighbour and write 20 % more bytes than the codes have (with both kinds per channel 1.21 -> 1.18 ms).
+constexpr int kResidentThreads = 512;
+constexpr int kResidentAtoms = 16;
+constexpr int kResidentRegs = 46;  // loads of a thread that wait in registers
+constexpr int kResidentLds = 18;   // ... in LDS
+constexpr int kResidentLoads = kResidentRegs + kResidentLds;
+constexpr int kResidentGroup = 6;  // loads in flight while the LDS slots are filled
+static_assert(kResidentLds % kResidentGroup == 0, "the LDS slots are filled a whole group of loads at a time");
 
 template <int DT>
 __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, uint32_t unit,
                                                            float (*red_lo)[kMaxStripAtoms * 8],
-                                                           float (*red_hi)[kMaxStripAtoms * 8]) {
-  constexpr int NI = kResidentLoads;
+                                                           float (*red_hi)[kMaxStripAtoms * 8], u32x4* stash) {
+  constexpr int NI = kResidentLoads, NR = kResidentRegs, NS = kResidentLds;
   const Geo& g = p.g;
   uint32_t uu = unit;
   const uint32_t strip = uu % (uint32_t)p.n_strips;
@@ -502,7 +565,8 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
   const uint8_t* srcb = reinterpret_cast<const uint8_t*>(p.kv + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts);
   const uint32_t ts2 = (uint32_t)p.ts * 2u;
 
-  u32x4 v[NI];
+  u32x4 v[NR];                       // loads NS .. NI-1
+  u32x4* const mine = stash + tid;   // load i < NS: mine[i * blockDim.x]
   float mnv[8], inv[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) mnv[i] = inv[i] = 0.f;
@@ -510,15 +574,30 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
   if (n > 0) {
     // byte offsets grow by a constant per pass; rows past the last token repeat it (min / max unchanged)
     const uint32_t last = ((uint32_t)n - 1u) * ts2 + e * 2u, off_row = row * ts2 + e * 2u, off_step = rows * ts2;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const uint32_t off = off_row + (uint32_t)i * off_step;
-      v[i] = stream_load<u32x4>(srcb + (size_t)(off < last ? off : last));
-    }
     ColumnStats<DT> st;
     st.init();
+    // the loads that wait in LDS first, while the registers of the others are still free to carry them
 #pragma unroll
-    for (int i = 0; i < NI; ++i) st.add(v[i]);
+    for (int i0 = 0; i0 < NS; i0 += kResidentGroup) {
+      u32x4 w[kResidentGroup];
+#pragma unroll
+      for (int u = 0; u < kResidentGroup; ++u) {
+        const uint32_t off = off_row + (uint32_t)(i0 + u) * off_step;
+        w[u] = stream_load<u32x4>(srcb + (size_t)(off < last ? off : last));
+      }
+#pragma unroll
+      for (int u = 0; u < kResidentGroup; ++u) {
+        st.add(w[u]);
+        mine[(uint32_t)(i0 + u) * blockDim.x] = w[u];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      const uint32_t off = off_row + (uint32_t)(NS + i) * off_step;
+      v[i] = stream_load<u32x4>(srcb + (size_t)(off < last ? off : last));
+    }
+#pragma unroll
+    for (int i = 0; i < NR; ++i) st.add(v[i]);
     for (uint32_t m = sa; m < 64u; m <<= 1) st.merge_xor((int)m);
     float lo[8], hi[8];
     st.get(lo, hi);
@@ -533,8 +612,8 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
     }
     __syncthreads();
     // one thread per channel of the strip finishes the reduction and derives the group's parameters
-    float* par_mn = &red_lo[kMaxWaves][0];
-    float* par_inv = &red_hi[kMaxWaves][0];
+    float* par_mn = &red_lo[n_waves][0];
+    float* par_inv = &red_hi[n_waves][0];
     if (tid < sa * 8u) {
       float l0 = red_lo[0][tid], h0 = red_hi[0][tid];
       for (uint32_t w = 1; w < n_waves; ++w) {
@@ -576,7 +655,10 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
     u32x2 o{0u, 0u};
     if (t < (uint32_t)n) {
       float x[8];
-      widen_atom<DT>(v[i], x);
+      if (i < NS)
+        widen_atom<DT>(mine[(uint32_t)i * blockDim.x], x);
+      else
+        widen_atom<DT>(v[i < NS ? 0 : i - NS], x);
       o = quantize_atom(x, mnv, inv);
     }
     uint32_t off = off0 + (uint32_t)i * pass_step;
@@ -664,10 +746,12 @@ __device__ __forceinline__ void pack_zero_body(const PackParams& p, uint32_t z) 
 }
 
 template <int DT, bool UNIFORM, bool RESIDENT>
-__global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
-  // partial column extremes of the waves; the last row carries the finished {mn} / {inv} of the strip
-  __shared__ float red_lo[kMaxWaves + 1][kMaxStripAtoms * 8];
-  __shared__ float red_hi[kMaxWaves + 1][kMaxStripAtoms * 8];
+__global__ void __launch_bounds__(RESIDENT ? kResidentThreads : 1024) pack_kernel(const PackParams p) {
+  // partial column extremes of the waves; the row after them carries the finished {mn} / {inv} of the strip
+  constexpr int kWaves = (RESIDENT ? kResidentThreads : 1024) / 64;
+  __shared__ float red_lo[kWaves + 1][kMaxStripAtoms * 8];
+  __shared__ float red_hi[kWaves + 1][kMaxStripAtoms * 8];
+  extern __shared__ u32x4 stash[];  // the loads of the per-channel bodies that wait in LDS, one slot per thread each
   // Workgroups go to the 8 XCDs round-robin.  Each XCD gets one contiguous range
   // of the per-channel units, one of the per-token units and one of the zero-fill
   // units, so neighbouring strips and token blocks share an L2 and every XCD has
@@ -677,17 +761,38 @@ __global__ void __launch_bounds__(1024) pack_kernel(const PackParams p) {
     const uint32_t unit = xcd * p.ch_per_xcd + idx;
     if (unit < p.n_units_ch) {
       if (RESIDENT)
-        pack_channel_body_resident<DT>(p, unit, red_lo, red_hi);
+        pack_channel_body_resident<DT>(p, unit, red_lo, red_hi, stash);
       else
-        pack_channel_body<DT>(p, unit, red_lo, red_hi);
+        pack_channel_body<DT>(p, unit, red_lo, red_hi, stash);
     }
   } else if (idx < p.ch_per_xcd + p.tok_per_xcd) {
     const uint32_t unit = xcd * p.tok_per_xcd + (idx - p.ch_per_xcd);
-    if (unit < p.n_units_tok) pack_token_body<DT, UNIFORM>(p, unit);
+    if (unit < p.n_units_tok) pack_token_body<DT, UNIFORM, RESIDENT ? KVC_PACK_U_RESIDENT : KVC_PACK_U>(p, unit);
   } else {
     const uint32_t unit = xcd * p.zero_per_xcd + (idx - p.ch_per_xcd - p.tok_per_xcd);
     if (unit < p.n_units_zero) pack_zero_body(p, unit);
   }
+}
+
+// The per-channel bodies ask for more dynamic LDS than the 64 KB a kernel gets unasked; the limit of a kernel
+// is raised once per device (devices beyond the 64 the mask covers: on every launch).
+template <int DT, bool UNIFORM, bool RESIDENT>
+hipError_t launch_variant(dim3 grid, dim3 block, size_t lds, hipStream_t stream, const PackParams& p) {
+  static std::atomic<uint64_t> raised{0};
+  const auto fn = pack_kernel<DT, UNIFORM, RESIDENT>;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = dev < 64 ? 1ull << dev : 0ull;
+  if ((raised.load(std::memory_order_acquire) & bit) == 0) {
+    constexpr size_t most = RESIDENT ? (size_t)kResidentLds * kResidentThreads * sizeof(u32x4)
+                                     : (size_t)kStreamStashLoads * 1024 * sizeof(u32x4);
+    e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
+    if (e != hipSuccess) return e;
+    raised.fetch_or(bit, std::memory_order_release);
+  }
+  hipLaunchKernelGGL(fn, grid, block, lds, stream, p);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -706,10 +811,9 @@ kvc_status plan_pack(PackParams& p, int* threads_out) {
   // per-token part: a whole number of tokens per pass, about 256 threads
   const int glanes = g.D / 8;
   if (p.n_kinds_tok > 0 && (glanes > 64 || (glanes & (glanes - 1)) != 0)) return KVC_ERR_UNSUPPORTED;
-  // Per-channel kinds whose chunk fits the register-resident strip run with 1024
-  // threads (the strip then spans 128 token rows x 16 loads = 2048 tokens).
-  constexpr int kResidentThreads = 1024;
-  p.strip_atoms = 8;  // 64 channels: 128-byte input rows, 64-byte code rows
+  // Per-channel kinds whose chunk fits the resident strip run with 512 threads (the strip then spans 32 token
+  // rows x 64 loads = 2048 tokens of 128 channels: 256-byte input rows, 128-byte code rows).
+  p.strip_atoms = kResidentAtoms;
   // The resident body forms 32-bit byte offsets for all kResidentLoads x rows token rows of a strip, whatever
   // the chunk length (rows past the last token are clamped afterwards), and inside the chunk's frame section.
   const int64_t resident_rows = (int64_t)kResidentLoads * (kResidentThreads / p.strip_atoms);
@@ -717,9 +821,10 @@ kvc_status plan_pack(PackParams& p, int* threads_out) {
                        g.frame_bytes < (1ll << 32)
                    ? 1
                    : 0;
-  // Chunks too long for that stream each strip twice.  Few, large workgroups keep the strips in flight few
-  // (one 1024-thread workgroup per CU), so that part of the second read still finds its strip in the
-  // last-level cache: 10 240-token chunks pack in 1.40 ms this way against 1.83 ms with 256-thread workgroups.
+  // Chunks too long for that read the part of each strip that does not fit on chip twice.  Few, large
+  // workgroups (one of 1024 threads per CU) give each strip the whole CU's registers and LDS to wait in, and
+  // keep the strips in flight few, so that part of the second read still finds its strip in the last-level
+  // cache: 10 240-token chunks pack in 1.37 ms this way against 1.83 ms with 256-thread workgroups.
 #ifndef KVC_PACK_STREAM_THREADS
 #define KVC_PACK_STREAM_THREADS 1024
 #endif
@@ -773,7 +878,9 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
   const Geo& g = p.g;
   const dim3 grid(p.units_per_xcd * 8u), block((unsigned)threads);
   const bool uniform = g.apt % 64 == 0;
-#define KVC_LAUNCH_PACK(DT_, UNI_, RES_) hipLaunchKernelGGL((pack_kernel<DT_, UNI_, RES_>), grid, block, 0, stream, p)
+  const size_t lds = (size_t)(p.resident ? kResidentLds : kStreamStashLoads) * threads * sizeof(u32x4);
+  hipError_t err = hipSuccess;
+#define KVC_LAUNCH_PACK(DT_, UNI_, RES_) err = launch_variant<DT_, UNI_, RES_>(grid, block, lds, stream, p)
   if (g.dtype == KVC_F16) {
     if (uniform) {
       if (p.resident) KVC_LAUNCH_PACK(KVC_F16, true, true); else KVC_LAUNCH_PACK(KVC_F16, true, false);
@@ -788,7 +895,7 @@ kvc_status launch_pack(PackParams p, hipStream_t stream) {
     }
   }
 #undef KVC_LAUNCH_PACK
-  return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_RUNTIME;
+  return err == hipSuccess ? KVC_OK : KVC_ERR_RUNTIME;
 }
 
 }  // namespace kvc

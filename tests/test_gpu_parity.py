@@ -80,12 +80,15 @@ def test_small_geometries(shape, modes, dtype):
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("modes", [(0, 1), (0, 0)])
-def test_long_chunks_take_the_two_pass_strip_body(dtype, modes):
+@pytest.mark.parametrize("T", [2560, 3584, 4100])
+def test_long_chunks_take_the_two_pass_strip_body(dtype, modes, T):
     """Chunks longer than the 2048 tokens a register-resident strip holds (the paper's chunks are 10K tokens,
-    Sec. 4 item (1)): the per-channel kinds then stream their strip twice."""
-    L, H, D, T, n, bs = 2, 8, 128, 2560, 2560 + 333, 16
+    Sec. 4 item (1)): the per-channel kinds then keep the last 3072 tokens of a strip on chip (registers and LDS) and
+    stream what comes before twice.  The streamed part is empty (2560), one exact step of its loop (512 tokens),
+    two steps and a ragged one (1028); the short last chunk fills the on-chip part only partly."""
+    L, H, D, n, bs = 2, 8, 128, T + 333, 16
     glo, olo = hz.layouts(L, H, D, dtype, T, 8, 128, 8, 40, *modes)
-    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=2560, device="cuda")
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=T, device="cuda")
     full_check(glo, olo, kv, n, dtype, block_size=bs, tag="long chunk")
 
 

@@ -278,7 +278,7 @@ def test_pack_keeps_strips_resident_only_while_32_bit_row_offsets_hold(kvc_lib):
     streaming body instead."""
     C = 1024
     dense = (2 * 4096 * C, 4096 * C, C)
-    assert kvc.pack_plan(good(), dense) == (1, 1024)
+    assert kvc.pack_plan(good(), dense) == (1, 512)
     assert kvc.pack_plan(good(chunk_tokens=1024, tiles_y=32), dense)[0] == 1
     assert kvc.pack_plan(good(chunk_tokens=4096, tiles_y=128), dense)[0] == 0          # chunk longer than a strip
     assert kvc.pack_plan(good(k_mode=1), dense)[0] == 0                                 # nothing per channel
