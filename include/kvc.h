@@ -432,9 +432,23 @@ int32_t kvc_tile_candidates(int32_t num_kv_heads, int32_t head_dim, int32_t* til
  *                entries must be < out_bytes / piece_bytes (not checked: they
  *                are device memory).  NULL: sequential output.
  *   piece_bytes  a power of two, 32768 .. 2^30, dividing out_bytes
- *   wg_bytes     output bytes one workgroup moves in one shot: 4096 or 32768 */
+ *   wg_bytes     output bytes one workgroup moves in one shot: 4096 or 32768
+ *   shape        0, or KVC_PROBE_* bits; any bit needs wg_bytes 4096 and out_bytes
+ *                a multiple of 32768
+ * Output vector j (16 bytes, source order) is {x, y, x ^ y, s}, (x, y) being source
+ * vector s (8 bytes); s = j unless KVC_PROBE_LINE_READS pairs them otherwise. */
+enum {
+  /* The 8 workgroups that write one 32 KB run of the output run on one XCD
+   * (workgroups go to the XCDs round-robin) instead of one on each. */
+  KVC_PROBE_ONE_XCD_PER_PIECE = 1,
+  /* A workgroup reads its 2 KB as 16 lines of 128 bytes 1 KB apart, the way the
+   * codes of two tokens lie in a frame of (8,128) tiles, 8 tiles wide (Sec. 3.2.1
+   * step 3): workgroup 8k+m reads lines m, m+8, .. of the 16 KB its group of 8
+   * reads together; s = (j / 2048) * 2048 + (j / 256 % 8 + 8 * (j % 256 / 16)) * 16 + j % 16. */
+  KVC_PROBE_LINE_READS = 2
+};
 kvc_status kvc_probe_expand(const void* d_src, void* d_dst, size_t out_bytes, const uint32_t* d_piece_map,
-                            size_t piece_bytes, int32_t wg_bytes, void* stream);
+                            size_t piece_bytes, int32_t wg_bytes, int32_t shape, void* stream);
 
 const char* kvc_status_str(kvc_status status);
 

@@ -9,5 +9,5 @@ from .kvc import (  # noqa: F401
     admission_min_buffered, admission_ok, blob_meta_offset, chunk_sizes, est_bandwidth, frame_offset, frame_size,
     layout_set_resolution, meta_staging_size, pack_plan, build_id, select_resolution, kvc_fetch_pipeline, kvc_fetch_pipeline_frames, kvc_pack, kvc_restore, kvc_restore_paged,
     kvc_restore_paged_frame, kvc_restore_paged_frames, layout_validate, lib_path, load, status_str, N_RESIDUALS, residual_histograms_size,
-    kvc_residual_histograms, proxy_cost_bits, tile_candidates, kvc_probe_expand,
+    kvc_residual_histograms, proxy_cost_bits, tile_candidates, kvc_probe_expand, PROBE_ONE_XCD_PER_PIECE, PROBE_LINE_READS,
 )

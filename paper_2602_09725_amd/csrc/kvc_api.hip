@@ -340,8 +340,10 @@ int32_t kvc_tile_candidates(int32_t num_kv_heads, int32_t head_dim, int32_t* til
 }
 
 kvc_status kvc_probe_expand(const void* d_src, void* d_dst, size_t out_bytes, const uint32_t* d_piece_map,
-                            size_t piece_bytes, int32_t wg_bytes, void* stream) {
+                            size_t piece_bytes, int32_t wg_bytes, int32_t shape, void* stream) {
   if (wg_bytes != 4096 && wg_bytes != 32768) return KVC_ERR_INVALID_ARG;
+  if ((shape & ~(KVC_PROBE_ONE_XCD_PER_PIECE | KVC_PROBE_LINE_READS)) != 0) return KVC_ERR_INVALID_ARG;
+  if (shape != 0 && (wg_bytes != 4096 || out_bytes % (8 * 4096) != 0)) return KVC_ERR_INVALID_ARG;
   if (piece_bytes < 32768 || (piece_bytes & (piece_bytes - 1)) != 0 || piece_bytes > ((size_t)1 << 30)) return KVC_ERR_INVALID_ARG;
   if (out_bytes % piece_bytes != 0 || out_bytes / piece_bytes > 0xffffffffull) return KVC_ERR_INVALID_ARG;
   if (out_bytes == 0) return KVC_OK;
@@ -349,7 +351,7 @@ kvc_status kvc_probe_expand(const void* d_src, void* d_dst, size_t out_bytes, co
     return KVC_ERR_INVALID_ARG;
   uint32_t log2_piece = 0;
   while (((size_t)1 << log2_piece) < piece_bytes) ++log2_piece;
-  return launch_probe_expand(d_src, d_dst, out_bytes, d_piece_map, log2_piece, wg_bytes, as_stream(stream));
+  return launch_probe_expand(d_src, d_dst, out_bytes, d_piece_map, log2_piece, wg_bytes, shape, as_stream(stream));
 }
 
 size_t kvc_frame_size(const kvc_layout* layout) {

@@ -101,8 +101,9 @@ struct ScoreParams {
 kvc_status launch_residual_histograms(ScoreParams p, hipStream_t stream);
 
 // Enqueues the reference expand copy (measurement aid): out_bytes / 2 bytes of src -> out_bytes of dst, piece i
-// of 2^log2_piece output bytes going to position piece_map[i] (nullptr: in place); wg_bytes is 4096 or 32768.
+// of 2^log2_piece output bytes going to position piece_map[i] (nullptr: in place); wg_bytes is 4096 or 32768;
+// shape: KVC_PROBE_* bits (4 KB workgroups, a multiple of 8 of them).
 kvc_status launch_probe_expand(const void* src, void* dst, size_t out_bytes, const uint32_t* piece_map, uint32_t log2_piece,
-                               int32_t wg_bytes, hipStream_t stream);
+                               int32_t wg_bytes, int32_t shape, hipStream_t stream);
 
 }  // namespace kvc

@@ -102,7 +102,7 @@ def load(path=None):
     ip = C.POINTER(i32)
     lib.kvc_tile_candidates.argtypes = [i32, i32, ip, ip, ip, i32]
     lib.kvc_tile_candidates.restype = i32
-    lib.kvc_probe_expand.argtypes = [vp, vp, sz, vp, sz, i32, vp]
+    lib.kvc_probe_expand.argtypes = [vp, vp, sz, vp, sz, i32, i32, vp]
     if path is None:
         _lib = lib
     return lib
@@ -160,8 +160,11 @@ def kvc_restore_paged(layout, frames_ptr, meta_ptr, first_token, n_tokens, layer
                                     stream), "kvc_restore_paged")
 
 
-def kvc_probe_expand(src_ptr, dst_ptr, out_bytes, piece_map_ptr, piece_bytes, wg_bytes, stream=0):
-    _check(load().kvc_probe_expand(src_ptr, dst_ptr, out_bytes, piece_map_ptr, piece_bytes, wg_bytes, stream),
+PROBE_ONE_XCD_PER_PIECE, PROBE_LINE_READS = 1, 2
+
+
+def kvc_probe_expand(src_ptr, dst_ptr, out_bytes, piece_map_ptr, piece_bytes, wg_bytes, stream=0, shape=0):
+    _check(load().kvc_probe_expand(src_ptr, dst_ptr, out_bytes, piece_map_ptr, piece_bytes, wg_bytes, shape, stream),
            "kvc_probe_expand")
 
 

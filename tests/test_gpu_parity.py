@@ -712,22 +712,28 @@ def test_config_frame_pipeline_matches_chunk_restore():
 @pytest.mark.parametrize("wg", [4096, 32768])
 def test_reference_expand_copy_moves_every_vector_where_the_map_says(wg):
     """The measurement aid kvc_probe_expand: vector j of the source order lands in piece map[j / per_piece] at the
-    same offset, with and without a map; nothing outside the destination is written."""
+    same offset, with and without a map, whichever XCD its workgroup runs on; with line reads it carries the source
+    vector the header's formula pairs it with; nothing outside the destination is written."""
     out_bytes, piece = 3 << 20, 32768
     n_vec, per_piece = out_bytes // 16, piece // 16
     src = torch.randint(-2**31, 2**31 - 1, (n_vec, 2), dtype=torch.int32, device="cuda")
     guard = 1024
+    j = torch.arange(n_vec, device="cuda")
     for use_map in (False, True):
-        buf = torch.full((guard + n_vec * 4 + guard,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
-        dst = buf[guard:guard + n_vec * 4]
-        assert dst.data_ptr() % 16 == 0
-        pm = torch.randperm(out_bytes // piece, generator=torch.Generator().manual_seed(3)).to(torch.int32).cuda()
-        hz.kvc.kvc_probe_expand(src.data_ptr(), dst.data_ptr(), out_bytes, pm.data_ptr() if use_map else 0, piece, wg,
-                                hz.stream_handle())
-        torch.cuda.synchronize()
-        j = torch.arange(n_vec, device="cuda")
-        want = torch.stack([src[:, 0], src[:, 1], src[:, 0] ^ src[:, 1], j.to(torch.int32)], dim=1)
-        where = (pm.long()[j // per_piece] * per_piece + j % per_piece) if use_map else j
-        got = dst.view(n_vec, 4)[where]
-        assert torch.equal(got, want)
-        assert bool((buf[:guard] == 0x5A5A5A5A).all()) and bool((buf[guard + n_vec * 4:] == 0x5A5A5A5A).all())
+        for shape in ((0, 1, 2, 3) if wg == 4096 else (0,)):
+            buf = torch.full((guard + n_vec * 4 + guard,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+            dst = buf[guard:guard + n_vec * 4]
+            assert dst.data_ptr() % 16 == 0
+            pm = torch.randperm(out_bytes // piece, generator=torch.Generator().manual_seed(3)).to(torch.int32).cuda()
+            hz.kvc.kvc_probe_expand(src.data_ptr(), dst.data_ptr(), out_bytes, pm.data_ptr() if use_map else 0, piece, wg,
+                                    hz.stream_handle(), shape=shape)
+            torch.cuda.synchronize()
+            s = j
+            if shape & hz.kvc.PROBE_LINE_READS:
+                s = (j // 2048) * 2048 + ((j // 256) % 8 + 8 * ((j % 256) // 16)) * 16 + j % 16
+                assert torch.equal(torch.sort(s).values, j)   # every source vector is read exactly once
+            want = torch.stack([src[s, 0], src[s, 1], src[s, 0] ^ src[s, 1], s.to(torch.int32)], dim=1)
+            where = (pm.long()[j // per_piece] * per_piece + j % per_piece) if use_map else j
+            got = dst.view(n_vec, 4)[where]
+            assert torch.equal(got, want), (use_map, shape)
+            assert bool((buf[:guard] == 0x5A5A5A5A).all()) and bool((buf[guard + n_vec * 4:] == 0x5A5A5A5A).all())

@@ -344,12 +344,13 @@ def test_residual_histograms_reject_bad_arguments(kvc_lib):
 
 def test_probe_expand_rejects_bad_arguments(kvc_lib):
     A = 0x7F0000000000
-    ok = dict(out=1 << 20, mp=0, piece=32768, wg=4096)
+    ok = dict(out=1 << 20, mp=0, piece=32768, wg=4096, shape=0)
     for kw, status in ((dict(wg=8192), 1), (dict(piece=4096), 1), (dict(piece=48 * 1024), 1), (dict(out=(1 << 20) + 4096), 1),
-                       (dict(src=0), 1), (dict(dst=A + 8), 1), (dict(mp=A + 2), 1)):
+                       (dict(src=0), 1), (dict(dst=A + 8), 1), (dict(mp=A + 2), 1), (dict(shape=4), 1),
+                       (dict(shape=1, wg=32768), 1), (dict(shape=2, wg=32768), 1)):
         a = dict(ok, src=A, dst=A)
         a.update(kw)
         with pytest.raises(kvc.KvcError) as e:
-            kvc.kvc_probe_expand(a["src"], a["dst"], a["out"], a["mp"], a["piece"], a["wg"])
+            kvc.kvc_probe_expand(a["src"], a["dst"], a["out"], a["mp"], a["piece"], a["wg"], shape=a["shape"])
         assert e.value.status == status, kw
     kvc.kvc_probe_expand(A, A, 0, 0, 32768, 4096)   # nothing to do
