@@ -217,7 +217,14 @@ kvc_status kvc_restore_paged(const kvc_layout* layout, const uint8_t* frames, co
  *   chunks            HOST array of n_chunks descriptors (blobs PINNED HOST)
  *   d_staging         HOST array of n_staging DEVICE buffers, each >= blob size
  *   staging_bytes     capacity of each staging buffer
- *   n_staging         >= 2
+ *   n_staging         2..64, or 0: nothing is copied, the restore kernels read
+ *                     the blobs in place over the host link (the blobs must then
+ *                     be mapped into the device, as hipHostMalloc memory is, and
+ *                     8-byte aligned; d_staging, staging_bytes and copy_stream
+ *                     are not looked at).  With tiles narrower than 512 bytes in
+ *                     rows of tiles of at least 512 the kernel's reads are long
+ *                     enough to draw the link's full rate, and this form is the
+ *                     faster one
  *   copy_stream, compute_stream : two distinct non-NULL hipStream_t
  *   fetch_to_ready_ms HOST out, may be NULL.  If non-NULL the call blocks until
  *                     the last restore has finished and stores the time from

@@ -48,6 +48,17 @@ kvc_status check_layout(const kvc_layout* lo) {
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// Whether p is host memory that is mapped into the device, so that a kernel reads it over the host link.
+// (A pointer the runtime does not know leaves an error behind, which is cleared: it is not this call's to report.)
+bool in_host_memory(const void* p) {
+  hipPointerAttribute_t a;
+  if (hipPointerGetAttributes(&a, p) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return a.type == hipMemoryTypeHost;
+}
+
 // Entropy in bits per symbol of a 256-bin histogram (0 for an empty one).
 double histogram_entropy(const uint64_t* bins) {
   double n = 0.0;
@@ -237,6 +248,7 @@ kvc_status kvc_restore(const kvc_layout* layout, const uint8_t* frames, const vo
   p.ks = strides.kv_stride;
   p.ts = strides.token_stride;
   p.dbs = make_fastdiv(1);
+  p.host_frames = !p.frame_mode && in_host_memory(p.frames);
   return launch_restore(p, false, as_stream(stream));
 }
 
@@ -278,6 +290,7 @@ kvc_status kvc_restore_paged(const kvc_layout* layout, const uint8_t* frames, co
   if (!aligned(frames, 16) || !aligned(meta, 8)) return KVC_ERR_INVALID_ARG;
   p.frames = frames;
   p.meta = static_cast<const float*>(meta);
+  p.host_frames = !p.frame_mode && in_host_memory(p.frames);
   return launch_restore(p, true, as_stream(stream));
 }
 
@@ -399,6 +412,7 @@ kvc_status kvc_restore_paged_frames(const kvc_layout* layout, const uint8_t* fra
                        d_err)) != KVC_OK)
     return st;
   if ((st = fill_frames_args(p, frames, meta, first_frame, n_frames, n_tokens)) != KVC_OK) return st;
+  p.host_frames = !p.frame_mode && in_host_memory(p.frames);
   return launch_restore(p, true, as_stream(stream));
 }
 
@@ -791,14 +805,19 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
     if (fetch_to_ready_ms) *fetch_to_ready_ms = 0.f;
     return KVC_OK;
   }
-  if (!chunks || !d_staging || n_staging < 2 || n_staging > 64) return KVC_ERR_INVALID_ARG;
-  if (!copy_stream || !compute_stream || copy_stream == compute_stream) return KVC_ERR_INVALID_ARG;
+  // n_staging == 0: no copies at all, the restore kernels read the blobs where they are
+  const bool in_place = n_staging == 0;
+  if (!chunks || !compute_stream) return KVC_ERR_INVALID_ARG;
+  if (!in_place) {
+    if (!d_staging || n_staging < 2 || n_staging > 64) return KVC_ERR_INVALID_ARG;
+    if (!copy_stream || copy_stream == compute_stream) return KVC_ERR_INVALID_ARG;
+  }
   const size_t meta_off = kvc_blob_meta_offset(layout);
   const size_t blob_bytes = meta_off + (size_t)base.g.meta_floats * 4;
-  if (staging_bytes < blob_bytes) return KVC_ERR_BUFFER_TOO_SMALL;
+  if (!in_place && staging_bytes < blob_bytes) return KVC_ERR_BUFFER_TOO_SMALL;
   int64_t total = 0;
   for (int i = 0; i < n_chunks; ++i) {
-    if (!chunks[i].host_blob) return KVC_ERR_INVALID_ARG;
+    if (!chunks[i].host_blob || (in_place && !aligned(chunks[i].host_blob, 8))) return KVC_ERR_INVALID_ARG;
     if (chunks[i].bytes < blob_bytes) return KVC_ERR_BUFFER_TOO_SMALL;
     if (chunks[i].n_tokens < 1 || chunks[i].n_tokens > base.g.T) return KVC_ERR_INVALID_ARG;
     if (i + 1 < n_chunks && chunks[i].n_tokens != base.g.T) return KVC_ERR_INVALID_ARG;
@@ -812,6 +831,7 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
 
   hipStream_t cs = as_stream(copy_stream), xs = as_stream(compute_stream);
   // Per staging slot: "copied" after the copy into it, "slot free" after the restore that read it.
+  if (in_place) cs = xs;  // the only stream in use
   EventLease ev(2 * n_staging, fetch_to_ready_ms ? 2 : 0);
   bool ok = ev.ok();
   const auto copied = [&](int slot) { return ev.sync(slot); };
@@ -823,16 +843,21 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
   if (ok) {
     if (t_begin) ok = hipEventRecord(t_begin, cs) == hipSuccess;
     for (int i = 0; i < n_chunks && ok; ++i) {
-      const int s = i % n_staging;
-      // the copy into slot s must wait for the restore that last read it
-      if (i >= n_staging) ok = hipStreamWaitEvent(cs, freed(s), 0) == hipSuccess;
-      if (ok) ok = hipMemcpyAsync(d_staging[s], chunks[i].host_blob, blob_bytes, hipMemcpyHostToDevice, cs) == hipSuccess;
-      if (ok) ok = hipEventRecord(copied(s), cs) == hipSuccess;
-      if (ok) ok = hipStreamWaitEvent(xs, copied(s), 0) == hipSuccess;
-      if (!ok) break;
+      const int s = in_place ? 0 : i % n_staging;
+      const void* blob = chunks[i].host_blob;
+      if (!in_place) {
+        // the copy into slot s must wait for the restore that last read it
+        if (i >= n_staging) ok = hipStreamWaitEvent(cs, freed(s), 0) == hipSuccess;
+        if (ok) ok = hipMemcpyAsync(d_staging[s], chunks[i].host_blob, blob_bytes, hipMemcpyHostToDevice, cs) == hipSuccess;
+        if (ok) ok = hipEventRecord(copied(s), cs) == hipSuccess;
+        if (ok) ok = hipStreamWaitEvent(xs, copied(s), 0) == hipSuccess;
+        if (!ok) break;
+        blob = d_staging[s];
+      }
       RestoreParams p = base;
-      p.frames = static_cast<const uint8_t*>(d_staging[s]);
-      p.meta = reinterpret_cast<const float*>(static_cast<const uint8_t*>(d_staging[s]) + meta_off);
+      p.host_frames = in_place;
+      p.frames = static_cast<const uint8_t*>(blob);
+      p.meta = reinterpret_cast<const float*>(static_cast<const uint8_t*>(blob) + meta_off);
       p.first_token = (int64_t)i * base.g.T;
       p.n_tokens = chunks[i].n_tokens;
       const kvc_status ls = launch_restore(p, true, xs);
@@ -841,7 +866,7 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
         ok = false;
         break;
       }
-      ok = hipEventRecord(freed(s), xs) == hipSuccess;
+      if (!in_place) ok = hipEventRecord(freed(s), xs) == hipSuccess;
     }
     if (!ok && result == KVC_OK) result = KVC_ERR_RUNTIME;
     if (t_end) {

@@ -21,6 +21,10 @@ struct RestoreParams {
   FastDiv dtbc, dL;       // unit -> (token block, chunk), row -> (kind, layer)
   uint32_t row_units;     // chunk call: token blocks of one (kind, layer) over all chunks
   FastDiv drpx;           // ... and the share of one XCD
+  // chunk call, "rows" body: a wave reads runs of 512 bytes of one plane row, i.e. one row of rows_q = 512 / tw
+  // neighbouring tiles; a workgroup (th waves) takes one row of tiles in all F frames: TX * F tokens
+  int32_t rows_body, rows_q, rows_lat, rows_passes;  // lat: log2 of the atoms of a tile row; passes = F * TX / q
+  int32_t host_frames;    // `frames` is host memory mapped into the device: prefer the "rows" body
   FastDiv dapt;           // atoms per token
   FastDiv dwpt;           // waves per token (apt / 64) when apt is a multiple of 64
   uint32_t frame_stride;     // bytes from a frame to the next of the same layer group: 3 planes (0 for a frame call)

@@ -26,7 +26,7 @@ def _lib(kvc_lib):
     return kvc_lib
 
 
-def full_check(glo, olo, kv, n_tokens, dtype, block_size=None, table_seed=0, spare_blocks=3, tag=""):
+def full_check(glo, olo, kv, n_tokens, dtype, block_size=None, table_seed=0, spare_blocks=3, tag="", host_frames=False):
     """pack -> compare frames/meta; restore contiguous -> compare; restore paged -> compare placement."""
     hz.say(f"[case] {tag} L={olo.L} H={olo.H} D={olo.D} {dtype} T={olo.T} tile=({olo.th},{olo.tw}) grid=({olo.TX},{olo.TY}) "
            f"modes=({olo.k_mode},{olo.v_mode}) n_tokens={n_tokens} bs={block_size}")
@@ -53,6 +53,24 @@ def full_check(glo, olo, kv, n_tokens, dtype, block_size=None, table_seed=0, spa
         assert int(cache.err.item()) == 0
         for l, (got, want) in enumerate(zip(cache.numpy_layers(), want_caches)):
             hz.assert_same_bytes(f"paged layer {l}", got, want)
+    if host_frames:
+        # the same restores with frames and pairs left in pinned host memory (mapped into the device): tiles
+        # narrower than 512 bytes are then read by the body that walks plane rows
+        hf = torch.empty(frames.numel(), dtype=torch.uint8, pin_memory=True)
+        hm = torch.empty(meta.numel(), dtype=torch.float32, pin_memory=True)
+        assert hf.numel() == frames.numel() and hm.numel() * 4 == meta.numel() * meta.element_size()
+        hf.copy_(frames)
+        hm.copy_(meta)
+        torch.cuda.synchronize()
+        out = hz.gpu_restore(glo, hf, hm, n_tokens, TD[dtype])
+        neq = hz.assert_within_one_ulp("restore from host frames", hz.u16(out), want_out)
+        assert neq == 0
+        if block_size:
+            cache = hz.PagedCache(olo.L, num_blocks, block_size, C)
+            hz.gpu_restore_paged(glo, hf, hm, 0, n_tokens, cache, table.cuda())
+            assert int(cache.err.item()) == 0
+            for l, (got, want) in enumerate(zip(cache.numpy_layers(), want_caches)):
+                hz.assert_same_bytes(f"paged layer {l} from host frames", got, want)
     return frames, meta
 
 
@@ -76,6 +94,31 @@ def test_small_geometries(shape, modes, dtype):
     glo, olo = hz.layouts(L, H, D, dtype, T, th, tw, TX, TY, *modes)
     kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=1000 + L * 7 + H, device="cuda")
     full_check(glo, olo, kv, n, dtype, block_size=bs, tag="small")
+
+
+ROW_RUNS = [
+    # L, H, D, T, th, tw, seg, TX, TY, n_tokens, block_size: tiles narrower than 512 bytes in rows of tiles of >= 512
+    (4, 8, 128, 96, 8, 128, 0, 4, 8, 96 + 50, 16),       # the benchmark tile, one run per row, F = 3
+    (3, 8, 128, 300, 8, 128, 0, 8, 5, 300 * 2 + 7, 16),  # two runs per row, F = 8: 16 passes, two rounds of 8
+    (2, 8, 128, 64, 16, 64, 0, 8, 2, 64 + 9, 7),         # tile (16,64): 8 tiles per run, 1024 threads, odd block size
+    (5, 8, 128, 50, 4, 256, 0, 2, 9, 50 * 3, 32),        # tile (4,256): 2 tiles per run, 256 threads
+    (4, 8, 128, 96, 8, 128, 64, 4, 8, 96 + 50, 16),      # two-level (4,2)x(2,64): a tile row holds halves of two heads
+    (2, 4, 128, 70, 8, 64, 64, 8, 3, 70 + 33, 16),       # C = 512, two-level with d2 = 64
+    (3, 32, 128, 40, 16, 256, 128, 2, 5, 40 + 11, 16),   # 32 heads: tile (16,256) = (16,2)x(1,128)
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("modes", [(0, 1), (1, 0)])
+@pytest.mark.parametrize("shape", ROW_RUNS, ids=[f"r{i}" for i in range(len(ROW_RUNS))])
+def test_frames_left_in_pinned_host_memory(shape, modes, dtype):
+    """Restore, contiguous and paged, with frames and pairs in pinned host memory: chunk calls on these tiles take
+    the body whose waves read 512-byte runs along plane rows; same oracle comparison as everywhere else."""
+    L, H, D, T, th, tw, seg, TX, TY, n, bs = shape
+    glo, olo = hz.layouts(L, H, D, dtype, T, th, tw, TX, TY, modes[0], modes[1], seg=seg)
+    assert hz.kvc.layout_validate(glo) == 0
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=4000 + T + th, device="cuda")
+    full_check(glo, olo, kv, n, dtype, block_size=bs, tag="row runs", host_frames=True)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
@@ -411,6 +454,16 @@ def test_config_pipeline_matches_single_call():
         assert ms > 0 and int(cache.err.item()) == 0
         for l in range(w.L):
             assert torch.equal(cache.layers[l], ref.layers[l]), f"layer {l} differs from the single-call restore"
+    # no staging at all: the kernels read the pinned blobs in place (n_staging = 0, one stream)
+    cache = hz.PagedCache(w.L, n_logical, bs, C)
+    ms = kvc.kvc_fetch_pipeline(glo, [(b.data_ptr(), blob_bytes, T) for b in blobs], [], 0, cache.ptrs.data_ptr(),
+                                n_logical, bs, table.data_ptr(), n_logical, cache.err.data_ptr(), 0, s_comp.cuda_stream,
+                                timed=True)
+    torch.cuda.synchronize()
+    hz.say(f"[case] pipeline in place: fetch-to-ready {ms:.2f} ms")
+    assert ms > 0 and int(cache.err.item()) == 0
+    for l in range(w.L):
+        assert torch.equal(cache.layers[l], ref.layers[l]), f"in place: layer {l} differs from the single-call restore"
     # untimed form: returns after enqueueing, caller synchronizes
     cache = hz.PagedCache(w.L, n_logical, bs, C)
     r = kvc.kvc_fetch_pipeline(glo, [(b.data_ptr(), blob_bytes, T) for b in blobs], [s.data_ptr() for s in staging],

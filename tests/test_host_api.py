@@ -123,7 +123,10 @@ def test_data_calls_reject_bad_arguments_before_enqueueing(kvc_lib):
     blob = kvc.blob_meta_offset(lo) + mb
     pipe = lambda **k: status(kvc.kvc_fetch_pipeline, lo, k.get("chunks", chunks), k.get("staging", [A, A + 256]),
                               k.get("sb", blob), A, 512, 16, A, k.get("tl", 512), None, k.get("cs", 1), k.get("xs", 2))
-    assert pipe(staging=[A]) == 1                          # fewer than two staging slots
+    assert pipe(staging=[A]) == 1                          # one staging slot: neither staged nor in place
+    assert pipe(staging=[], chunks=[(A + 4, blob, 2048)]) == 1   # in place: the kernel loads 8 bytes at a time
+    assert pipe(staging=[], xs=0) == 1
+    assert pipe(staging=[], chunks=[(A, blob - 1, 2048)]) == 3
     assert pipe(sb=blob - 1) == 3
     assert pipe(chunks=[(A, blob - 1, 2048)]) == 3
     assert pipe(chunks=[(A, blob, 100), (A, blob, 2048)]) == 1   # only the last chunk may be short
