@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # this command, not in this one, and are keyed by the identifier the library carries (a hash of its sources,
 # header and compiler flags): for any other build the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "41c579c9da5e5c00": {"pack": 6582033176, "restore": 6513938259},
+    "f9d34e44aa6df3d4": {"pack": 6582179876, "restore": 6513950827},
 }
 TRAFFIC_PROFILE = "profiles/pack_restore_llama3_8b_32k_paged.txt"
 
