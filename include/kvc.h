@@ -297,7 +297,14 @@ size_t kvc_meta_staging_size(const kvc_layout* layout, int32_t order);
  * 2*F frames receives the K and the V frames of a (chunk, layer group) in one
  * two-row strided copy.
  *   d_frame_staging  HOST array of n_frame_staging (2..64) DEVICE buffers of
- *                    frame_staging_bytes >= kvc_frame_size, 256-byte aligned
+ *                    frame_staging_bytes >= kvc_frame_size, 256-byte aligned.
+ *                    n_frame_staging = 0: nothing is copied; every run of
+ *                    frames (a whole chunk in KVC_ORDER_CHUNK, the K and the V
+ *                    frames of a (chunk, layer group) in KVC_ORDER_LAYER) is
+ *                    restored by a kernel that reads the blob in place over the
+ *                    host link, on compute_stream alone (blobs mapped into the
+ *                    device and 8-byte aligned; both staging arrays, their sizes
+ *                    and copy_stream are not looked at)
  *   d_meta_staging   HOST array of n_meta_staging (2..64) DEVICE buffers of
  *                    meta_staging_bytes >= kvc_meta_staging_size(layout, order),
  *                    256-byte aligned

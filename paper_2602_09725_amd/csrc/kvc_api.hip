@@ -248,7 +248,7 @@ kvc_status kvc_restore(const kvc_layout* layout, const uint8_t* frames, const vo
   p.ks = strides.kv_stride;
   p.ts = strides.token_stride;
   p.dbs = make_fastdiv(1);
-  p.host_frames = !p.frame_mode && in_host_memory(p.frames);
+  p.host_frames = in_host_memory(p.frames);
   return launch_restore(p, false, as_stream(stream));
 }
 
@@ -290,7 +290,7 @@ kvc_status kvc_restore_paged(const kvc_layout* layout, const uint8_t* frames, co
   if (!aligned(frames, 16) || !aligned(meta, 8)) return KVC_ERR_INVALID_ARG;
   p.frames = frames;
   p.meta = static_cast<const float*>(meta);
-  p.host_frames = !p.frame_mode && in_host_memory(p.frames);
+  p.host_frames = in_host_memory(p.frames);
   return launch_restore(p, true, as_stream(stream));
 }
 
@@ -395,7 +395,9 @@ kvc_status fill_frames_args(RestoreParams& p, const uint8_t* frames, const void*
   p.meta = static_cast<const float*>(meta);
   p.frame_mode = 1;
   p.fm_first = (int32_t)first_frame;
-  p.fm_count = (int32_t)n_frames;
+  p.fm_count = p.fm_count1 = (int32_t)n_frames;
+  p.fm_first2 = 0;
+  p.frames2 = nullptr;
   return KVC_OK;
 }
 
@@ -412,7 +414,7 @@ kvc_status kvc_restore_paged_frames(const kvc_layout* layout, const uint8_t* fra
                        d_err)) != KVC_OK)
     return st;
   if ((st = fill_frames_args(p, frames, meta, first_frame, n_frames, n_tokens)) != KVC_OK) return st;
-  p.host_frames = !p.frame_mode && in_host_memory(p.frames);
+  p.host_frames = in_host_memory(p.frames);
   return launch_restore(p, true, as_stream(stream));
 }
 
@@ -517,17 +519,22 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
       for (int lg = 0; lg < g.LG; ++lg) group_ready_ms[lg] = 0.f;
     return KVC_OK;
   }
-  if (!chunks || !d_frame_staging || !d_meta_staging) return KVC_ERR_INVALID_ARG;
-  if (n_frame_staging < 2 || n_frame_staging > 64 || n_meta_staging < 2 || n_meta_staging > 64) return KVC_ERR_INVALID_ARG;
-  if (!copy_stream || !compute_stream || copy_stream == compute_stream) return KVC_ERR_INVALID_ARG;
+  // n_frame_staging == 0: nothing is copied, the kernels read frames and pairs where they are
+  const bool in_place = n_frame_staging == 0;
+  if (!chunks || !compute_stream) return KVC_ERR_INVALID_ARG;
+  if (!in_place) {
+    if (!d_frame_staging || !d_meta_staging) return KVC_ERR_INVALID_ARG;
+    if (n_frame_staging < 2 || n_frame_staging > 64 || n_meta_staging < 2 || n_meta_staging > 64) return KVC_ERR_INVALID_ARG;
+    if (!copy_stream || copy_stream == compute_stream) return KVC_ERR_INVALID_ARG;
+  }
   const size_t meta_off = kvc_blob_meta_offset(layout);
   const size_t meta_bytes = (size_t)g.meta_floats * 4, frame_size = (size_t)(3 * g.plane);
   const size_t blob_bytes = meta_off + meta_bytes;
-  if (frame_staging_bytes < frame_size || meta_staging_bytes < kvc_meta_staging_size(layout, order))
+  if (!in_place && (frame_staging_bytes < frame_size || meta_staging_bytes < kvc_meta_staging_size(layout, order)))
     return KVC_ERR_BUFFER_TOO_SMALL;
   int64_t total = 0;
   for (int i = 0; i < n_chunks; ++i) {
-    if (!chunks[i].host_blob) return KVC_ERR_INVALID_ARG;
+    if (!chunks[i].host_blob || (in_place && !aligned(chunks[i].host_blob, 8))) return KVC_ERR_INVALID_ARG;
     if (chunks[i].bytes < blob_bytes) return KVC_ERR_BUFFER_TOO_SMALL;
     if (chunks[i].n_tokens < 1 || chunks[i].n_tokens > g.T) return KVC_ERR_INVALID_ARG;
     if (i + 1 < n_chunks && chunks[i].n_tokens != g.T) return KVC_ERR_INVALID_ARG;
@@ -535,7 +542,7 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
   }
   for (int s = 0; s < n_frame_staging; ++s)
     if (!d_frame_staging[s] || !aligned(d_frame_staging[s], 256)) return KVC_ERR_INVALID_ARG;
-  for (int s = 0; s < n_meta_staging; ++s)
+  for (int s = 0; s < n_meta_staging && !in_place; ++s)
     if (!d_meta_staging[s] || !aligned(d_meta_staging[s], 256)) return KVC_ERR_INVALID_ARG;
   if (group_ready_events)
     for (int lg = 0; lg < g.LG; ++lg)
@@ -545,6 +552,10 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
 
   hipStream_t cs = as_stream(copy_stream), xs = as_stream(compute_stream);
   const bool blocking = fetch_to_ready_ms || group_ready_ms;
+  if (in_place) {
+    cs = xs;  // the only stream in use
+    n_meta_staging = 0;
+  }
   // "copied" after the copies into a frame slot, "freed" after the last kernel that read a slot (frame slots, then
   // meta slots); with timing: begin, end, then one per layer group
   EventLease ev(2 * n_frame_staging + n_meta_staging, blocking ? 2 + (group_ready_ms ? g.LG : 0) : 0);
@@ -684,7 +695,47 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
     return true;
   };
 
-  if (ok) {
+  // In place: one launch per run of consecutive frames, or per two runs of the same length (the K and the V
+  // frames of a layer group, first2 > 0), reading the blob where it is.
+  auto restore_in_place = [&](int i, int64_t first, int64_t count, int64_t first2) {
+    if (!ok) return;
+    const uint8_t* blob = static_cast<const uint8_t*>(chunks[i].host_blob);
+    RestoreParams p = base;
+    p.first_token = (int64_t)i * g.T;
+    p.n_tokens = chunks[i].n_tokens;
+    p.host_frames = 1;
+    kvc_status ls = fill_frames_args(p, blob + (size_t)first * frame_size, blob + meta_off, first, count, chunks[i].n_tokens);
+    if (ls == KVC_OK && first2 > 0) {
+      p.fm_count = (int32_t)(2 * count);
+      p.fm_first2 = (int32_t)first2;
+      p.frames2 = blob + (size_t)first2 * frame_size;
+    }
+    if (ls == KVC_OK) ls = launch_restore(p, true, xs);
+    if (ls != KVC_OK) {
+      result = ls;
+      ok = false;
+    }
+  };
+  auto groups_ready = [&](int lg_first, int lg_end) {
+    for (int lg = lg_first; lg < lg_end && ok; ++lg) {
+      if (group_ready_events) ok = hipEventRecord(static_cast<hipEvent_t>(group_ready_events[lg]), xs) == hipSuccess;
+      if (ok && group_ready_ms) ok = hipEventRecord(t_group(lg), xs) == hipSuccess;
+    }
+  };
+
+  if (ok && in_place) {
+    if (t_begin) ok = hipEventRecord(t_begin, xs) == hipSuccess;
+    if (order == KVC_ORDER_CHUNK) {
+      for (int i = 0; i < n_chunks; ++i) restore_in_place(i, 0, per_chunk, 0);
+      groups_ready(0, g.LG);
+    } else {
+      for (int lg = 0; lg < g.LG && ok; ++lg) {
+        for (int i = 0; i < n_chunks; ++i)  // K and V frames of the group
+          restore_in_place(i, (int64_t)lg * g.F, g.F, ((int64_t)g.LG + lg) * g.F);
+        groups_ready(lg, lg + 1);
+      }
+    }
+  } else if (ok) {
     if (t_begin) ok = hipEventRecord(t_begin, cs) == hipSuccess;
     if (order == KVC_ORDER_CHUNK) {
       for (int i = 0; i < n_chunks && ok; ++i) {
@@ -702,6 +753,8 @@ kvc_status kvc_fetch_pipeline_frames(const kvc_layout* layout, const kvc_host_ch
         }
     }
     flush();
+  }
+  if (ev.ok()) {
     if (!ok && result == KVC_OK) result = KVC_ERR_RUNTIME;
     if (blocking) {
       if (hipEventRecord(t_end, xs) != hipSuccess || hipEventSynchronize(t_end) != hipSuccess) {

@@ -21,9 +21,11 @@ struct RestoreParams {
   FastDiv dtbc, dL;       // unit -> (token block, chunk), row -> (kind, layer)
   uint32_t row_units;     // chunk call: token blocks of one (kind, layer) over all chunks
   FastDiv drpx;           // ... and the share of one XCD
-  // chunk call, "rows" body: a wave reads runs of 512 bytes of one plane row, i.e. one row of rows_q = 512 / tw
-  // neighbouring tiles; a workgroup (th waves) takes one row of tiles in all F frames: TX * F tokens
-  int32_t rows_body, rows_q, rows_lat, rows_passes;  // lat: log2 of the atoms of a tile row; passes = F * TX / q
+  // "rows" body: a wave reads runs of 512 bytes of one plane row, i.e. one row of rows_q = 512 / tw neighbouring
+  // tiles; a workgroup (th waves) takes rows_trw rows of tiles, in all F frames (chunk call) or in one (frame call)
+  int32_t rows_body, rows_q, rows_lat;  // lat: log2 of the atoms of a tile row
+  int32_t rows_trw, rows_tile_rows;     // rows of tiles per workgroup; rows of tiles that hold tokens
+  FastDiv dnf, dpr;                     // frames a unit covers (F or 1); passes per row of tiles = that * TX / q
   int32_t host_frames;    // `frames` is host memory mapped into the device: prefer the "rows" body
   FastDiv dapt;           // atoms per token
   FastDiv dwpt;           // waves per token (apt / 64) when apt is a multiple of 64
@@ -31,6 +33,10 @@ struct RestoreParams {
   // frame call: `frames` holds fm_count consecutive frames (three planes each), the first being
   // frame number fm_first = (kind * LG + layer group) * F + frame index of its chunk
   int32_t frame_mode, fm_first, fm_count;
+  // ... of which the first fm_count1 are at `frames`; the others, if any, are a second run of consecutive frames
+  // that starts with frame number fm_first2 at `frames2`
+  int32_t fm_count1, fm_first2;
+  const uint8_t* frames2;
   FastDiv dLG;
   // Where the pairs of (kind, layer l) start: meta + chunk * meta_floats + moff[kind] + (l - meta_l0) * pairs per
   // layer * 2 floats.  A whole chunk section has meta_l0 = 0 and the section's own offsets (set by launch_restore

@@ -191,9 +191,11 @@ __device__ __forceinline__ uint32_t tile_elem(const Geo& g, uint32_t r, uint32_t
   return (a * g.dh2.d + b) * (uint32_t)g.D + c * (uint32_t)g.seg + i;
 }
 
+// Unit `tg` is a group of rows_trw rows of tiles of one (chunk, kind, layer), in all F frames (chunk call) or in
+// frame ff alone (frame call: fsec is then that frame's plane and frame_stride 0).
 template <int MODE, int DT, bool PAGED>
 __device__ __forceinline__ void restore_body_rows(const RestoreParams& p, uint32_t c, uint32_t kind, uint32_t l,
-                                                  uint32_t ty, const uint8_t* fsec) {
+                                                  uint32_t tg, const uint8_t* fsec, uint32_t ff) {
   constexpr int U = KVC_RESTORE_U;
   const Geo& g = p.g;
   const uint32_t lane = threadIdx.x & 63u;
@@ -206,7 +208,8 @@ __device__ __forceinline__ void restore_body_rows(const RestoreParams& p, uint32
   const int64_t left = p.n_tokens - chunk_first;
   const uint32_t n = left < (int64_t)g.T ? (uint32_t)left : (uint32_t)g.T;  // valid tokens of this chunk
   const uint32_t per_row = (uint32_t)g.TX * (uint32_t)g.F;                   // tokens of one row of tiles
-  if (ty * per_row >= n) return;
+  const uint32_t ty0 = tg * (uint32_t)p.rows_trw;                            // first row of tiles of this unit
+  if (ty0 >= (uint32_t)p.rows_tile_rows || ty0 * per_row + ff >= n) return;
 
   const float* mbase = p.meta + (int64_t)c * g.meta_floats + p.moff[kind];
   const uint32_t lm = l - (uint32_t)p.meta_l0;
@@ -222,10 +225,13 @@ __device__ __forceinline__ void restore_body_rows(const RestoreParams& p, uint32
     obase = reinterpret_cast<uint8_t*>(as_const(p.layer_cache)[l]) + ((int64_t)kind * p.num_blocks * p.dbs.d * g.C + e) * 2;
   else
     obase = reinterpret_cast<uint8_t*>(p.out + (int64_t)l * p.ls + (int64_t)kind * p.ks + chunk_first * p.ts + e);
-  const uint8_t* src = fsec + ((ty * (uint32_t)g.th + r) * (uint32_t)g.W + lane * 8u);
-  const uint32_t tile0 = ty * (uint32_t)g.TX + tl;  // the lane's tile in run 0 of the row
+  const uint8_t* src = fsec + ((ty0 * (uint32_t)g.th + r) * (uint32_t)g.W + lane * 8u);
+  const uint32_t tile0 = ty0 * (uint32_t)g.TX + tl;  // the lane's tile in run 0 of the unit's first row
   const uint32_t pos0 = (uint32_t)(p.first_token + chunk_first);
-  const uint32_t passes = (uint32_t)p.rows_passes;  // pass k: frame k % F, run k / F
+  // pass k: frame k % nf, run (k / nf) % runs of row of tiles k / (nf * runs); nf = F, or 1 in a frame call
+  const uint32_t rows_left = (uint32_t)p.rows_tile_rows - ty0;
+  const uint32_t passes = (rows_left < (uint32_t)p.rows_trw ? rows_left : (uint32_t)p.rows_trw) * p.dpr.d;
+  const uint32_t row_bytes = (uint32_t)g.th * (uint32_t)g.W;
   bool bad = false;
 
   for (uint32_t k0 = 0; k0 < passes; k0 += U) {
@@ -235,10 +241,11 @@ __device__ __forceinline__ void restore_body_rows(const RestoreParams& p, uint32
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t k = k0 + u < passes ? k0 + u : passes - 1;
-      uint32_t run, f;
-      fd_divmod(g.dF, k, run, f);
-      tok[u] = (tile0 + run * (uint32_t)p.rows_q) * (uint32_t)g.F + f;
-      code[u] = stream_load<u32x2>(src + ((size_t)f * p.frame_stride + run * 512u));
+      uint32_t j, kk, run, f;
+      fd_divmod(p.dpr, k, j, kk);    // row of tiles of the unit, pass inside the row
+      fd_divmod(p.dnf, kk, run, f);
+      tok[u] = (tile0 + j * (uint32_t)g.TX + run * (uint32_t)p.rows_q) * (uint32_t)g.F + f + ff;
+      code[u] = stream_load<u32x2>(src + ((size_t)f * p.frame_stride + j * row_bytes + run * 512u));
       if (MODE == KVC_Q_PER_TOKEN) {
         const uint32_t tp = tok[u] < n ? tok[u] : n - 1u;  // positions without a token: any pair in bounds
         sm[u] = *(const KVC_GLOBAL f32x2*)(mrow + (size_t)tp * ((uint32_t)g.H * 8u));
@@ -367,14 +374,23 @@ __global__ void __launch_bounds__(1024) restore_kernel(const RestoreParams p) {
     // `frames` holds fm_count consecutive frames, the first being number fm_first of its chunk in
     // the order [kind][layer group][frame of the group]; a frame carries the (up to) three layers
     // of its group, one per plane.
-    const uint32_t frel = rest / 3u, pl = rest - frel * 3u;
+    // A second run of frames (fm_first2, at frames2) may follow the first fm_count1 frames in the same launch.
+    uint32_t frel = rest / 3u;
+    const uint32_t pl = rest - frel * 3u;
+    const uint8_t* run = p.frames;
+    uint32_t fno = (uint32_t)p.fm_first + frel;
+    if (frel >= (uint32_t)p.fm_count1) {
+      frel -= (uint32_t)p.fm_count1;
+      fno = (uint32_t)p.fm_first2 + frel;
+      run = p.frames2;
+    }
     uint32_t q, lg;
-    fd_divmod(p.g.dF, (uint32_t)p.fm_first + frel, q, ff);
+    fd_divmod(p.g.dF, fno, q, ff);
     fd_divmod(p.dLG, q, kind, lg);
     l = lg * 3u + pl;
     c = 0;
     if (l >= (uint32_t)p.g.L) return;
-    fsec = p.frames + ((int64_t)frel * 3 + pl) * p.g.plane;
+    fsec = run + ((int64_t)frel * 3 + pl) * p.g.plane;
   } else {
     uint32_t row, within;
     fd_divmod(p.drpx, idx, row, within);
@@ -387,14 +403,14 @@ __global__ void __launch_bounds__(1024) restore_kernel(const RestoreParams p) {
   }
   if (p.g.mode[kind] == KVC_Q_PER_CHANNEL) {
     if (BODY == kBodyRows)
-      restore_body_rows<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi, fsec);
+      restore_body_rows<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
     else if (BODY == kBodyWaves)
       restore_body_waves<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
     else
       restore_body_lanes<KVC_Q_PER_CHANNEL, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
   } else {
     if (BODY == kBodyRows)
-      restore_body_rows<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi, fsec);
+      restore_body_rows<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
     else if (BODY == kBodyWaves)
       restore_body_waves<KVC_Q_PER_TOKEN, DT, PAGED>(p, c, kind, l, tbi, fsec, ff);
     else
@@ -428,7 +444,7 @@ kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream) {
   // the frames are read over the host link.  (On frames in HBM it is 0.5 % faster than "waves" when the blocks of
   // the cache are in order and 0.4 % slower under a random block table: 1.136 / 1.185 against 1.142 / 1.180 ms.)
   const int q = g.tw < 512 && 512 % g.tw == 0 ? 512 / g.tw : 0;
-  const bool rows = p.host_frames && waves && !p.frame_mode && q >= 2 && g.TX % q == 0 && g.th <= 16;
+  const bool rows = p.host_frames && waves && q >= 2 && g.TX % q == 0 && g.th <= 16;
   const int threads = rows ? g.th * 64 : g.apt * tpp;
   const int body = rows ? kBodyRows : waves ? kBodyWaves : kBodyLanes;
   p.rows_body = rows ? 1 : 0;
@@ -436,8 +452,12 @@ kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream) {
     p.rows_q = q;
     p.rows_lat = 0;
     while ((8 << p.rows_lat) < g.tw) ++p.rows_lat;
-    p.rows_passes = g.F * (g.TX / q);
-    p.tb = g.TX * g.F;  // a workgroup takes one row of tiles
+    const int nf = p.frame_mode ? 1 : g.F, per_row = nf * (g.TX / q);  // passes one row of tiles takes
+    p.dnf = make_fastdiv((uint32_t)nf);
+    p.dpr = make_fastdiv((uint32_t)per_row);
+    p.rows_trw = per_row >= KVC_RESTORE_U ? 1 : KVC_RESTORE_U / per_row;  // about one round of loads per wave
+    p.rows_tile_rows = (int32_t)(((g.T + g.F - 1) / g.F + g.TX - 1) / g.TX);  // rows of tiles that hold tokens
+    p.tb = p.rows_trw * g.TX * g.F;  // tokens (chunk call) a workgroup takes
   }
   p.tpp = tpp;
   p.dapt = make_fastdiv((uint32_t)g.apt);
@@ -460,8 +480,9 @@ kvc_status launch_restore(RestoreParams p, bool paged, hipStream_t stream) {
   p.dL = make_fastdiv((uint32_t)g.L);
   p.dLG = make_fastdiv((uint32_t)g.LG);
   dim3 grid, block((unsigned)threads);
+  if (rows) p.tbc = (p.rows_tile_rows + p.rows_trw - 1) / p.rows_trw;  // units of one (chunk, kind, layer) or plane
   if (p.frame_mode) {
-    p.tbc = ((g.T + g.F - 1) / g.F + p.tb - 1) / p.tb;  // slots of one frame
+    if (!rows) p.tbc = ((g.T + g.F - 1) / g.F + p.tb - 1) / p.tb;  // slots of one frame
     const int64_t units = (int64_t)p.fm_count * 3 * p.tbc;
     if (units > 0x7fffffff / 8) return KVC_ERR_UNSUPPORTED;
     p.n_units = (uint32_t)units;

@@ -122,6 +122,72 @@ def test_frames_left_in_pinned_host_memory(shape, modes, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", ROW_RUNS, ids=[f"r{i}" for i in range(len(ROW_RUNS))])
+def test_frame_calls_and_in_place_pipelines_on_host_blobs(shape, dtype):
+    """Blobs left in pinned host memory: runs of consecutive frames restored in place (random cuts of each chunk's
+    frame sequence), and both fetch pipelines with no staging, in both orders -- each against the oracle's paged
+    restore of the oracle's own frames."""
+    L, H, D, T, th, tw, seg, TX, TY, n, bs = shape
+    glo, olo = hz.layouts(L, H, D, dtype, T, th, tw, TX, TY, seg=seg)
+    C = H * D
+    kvc = hz.kvc
+    kv = kv_synth.make_kv(L, H, D, n, TD[dtype], seed=77 + n, device="cuda")
+    frames, meta = hz.gpu_pack(glo, kv, n)
+    fb, mb, F = kvc.chunk_sizes(glo)
+    fs = kvc.frame_size(glo)
+    per_chunk = fb // fs
+    n_chunks = (n + T - 1) // T
+    n_logical = (n_chunks * T + bs - 1) // bs
+    nb = n_logical + 1
+    tab = kv_synth.make_block_table(n_logical, nb, 8).cuda()
+    want_f, want_m = oracle.pack(olo, kv_synth.to_u16(kv.cpu()).reshape(-1), n)
+    hz.assert_same_bytes("frames", frames.cpu().numpy(), want_f)
+    want_caches, oerr = hz.oracle_paged(olo, want_f, want_m, 0, n, L, nb, bs, C, tab.cpu().numpy())
+    assert oerr == 0
+    moff = kvc.blob_meta_offset(glo)
+    blob_bytes = moff + mb
+    blobs = []
+    for c in range(n_chunks):
+        b = torch.zeros(blob_bytes, dtype=torch.uint8, pin_memory=True)
+        b[:fb].copy_(frames[c * fb:(c + 1) * fb])
+        b[moff:moff + mb].copy_(meta.view(torch.uint8)[c * mb:(c + 1) * mb])
+        blobs.append(b)
+    torch.cuda.synchronize()
+
+    def check(cache, what):
+        torch.cuda.synchronize()
+        assert int(cache.err.item()) == 0
+        for l, (got_l, want_l) in enumerate(zip(cache.numpy_layers(), want_caches)):
+            hz.assert_same_bytes(f"{what}: layer {l}", got_l, want_l)
+
+    rng = np.random.default_rng(n)
+    got = hz.PagedCache(L, nb, bs, C)
+    for c, b in enumerate(blobs):
+        nt = min(T, n - c * T)
+        cuts = sorted(set(rng.integers(1, per_chunk, size=3).tolist())) if per_chunk > 1 else []
+        for a, e in zip([0] + cuts, cuts + [per_chunk]):
+            kvc.kvc_restore_paged_frames(glo, b.data_ptr() + a * fs, b.data_ptr() + moff, a, e - a, c * T, nt,
+                                         got.ptrs.data_ptr(), nb, bs, tab.data_ptr(), tab.numel(), got.err.data_ptr(),
+                                         hz.stream_handle())
+    check(got, "frame ranges in place")
+    chunks = [(b.data_ptr(), blob_bytes, min(T, n - c * T)) for c, b in enumerate(blobs)]
+    s_comp = torch.cuda.Stream()
+    cache = hz.PagedCache(L, nb, bs, C)
+    torch.cuda.synchronize()
+    kvc.kvc_fetch_pipeline(glo, chunks, [], 0, cache.ptrs.data_ptr(), nb, bs, tab.data_ptr(), tab.numel(),
+                           cache.err.data_ptr(), 0, s_comp.cuda_stream, timed=True)
+    check(cache, "chunk pipeline in place")
+    for order in (kvc.KVC_ORDER_CHUNK, kvc.KVC_ORDER_LAYER):
+        cache = hz.PagedCache(L, nb, bs, C)
+        torch.cuda.synchronize()
+        ms, gms = kvc.kvc_fetch_pipeline_frames(glo, chunks, [], 0, [], 0, cache.ptrs.data_ptr(), nb, bs, tab.data_ptr(),
+                                                tab.numel(), cache.err.data_ptr(), 0, s_comp.cuda_stream, order=order,
+                                                timed=True, group_times=True)
+        assert gms == sorted(gms) and gms[-1] <= ms + 1e-3
+        check(cache, f"frame pipeline in place, order {order}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("modes", [(0, 1), (0, 0)])
 @pytest.mark.parametrize("T", [2560, 3584, 4100])
 def test_long_chunks_take_the_two_pass_strip_body(dtype, modes, T):
@@ -717,6 +783,23 @@ def test_config_frame_pipeline_matches_chunk_restore():
             assert gms[0] > ms / 2   # chunk order completes every group only in the last of 16 chunks
         for l in range(w.L):
             assert torch.equal(cache.layers[l], ref.layers[l]), f"layer {l} differs from the chunk-level restore"
+    # no staging at all (n_frame_staging = 0): every run of frames is restored by a kernel that reads the blob in place
+    for order in (kvc.KVC_ORDER_CHUNK, kvc.KVC_ORDER_LAYER):
+        cache = hz.PagedCache(w.L, n_logical, bs, C)
+        torch.cuda.synchronize()
+        ms, gms = kvc.kvc_fetch_pipeline_frames(glo, [(b.data_ptr(), blob_bytes, T) for b in blobs], [], 0, [], 0,
+                                                cache.ptrs.data_ptr(), n_logical, bs, table.data_ptr(), n_logical,
+                                                cache.err.data_ptr(), 0, s_comp.cuda_stream, order=order, timed=True,
+                                                group_times=True)
+        torch.cuda.synchronize()
+        hz.say(f"[case] frame pipeline in place, order={order}: fetch-to-ready {ms:.2f} ms, first/last group ready "
+               f"{gms[0]:.2f}/{gms[-1]:.2f} ms")
+        assert ms > 0 and int(cache.err.item()) == 0
+        assert gms == sorted(gms) and gms[-1] <= ms + 1e-3
+        if order == kvc.KVC_ORDER_LAYER:
+            assert gms[0] < ms / 4
+        for l in range(w.L):
+            assert torch.equal(cache.layers[l], ref.layers[l]), f"in place, order {order}: layer {l} differs"
     # caller-made events, call returns after enqueueing: once group g's event has fired its layers are complete
     cache = hz.PagedCache(w.L, n_logical, bs, C)
     events = [torch.cuda.Event() for _ in range(LG)]

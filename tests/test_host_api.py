@@ -173,6 +173,10 @@ def test_frame_calls_reject_bad_arguments(kvc_lib):
     assert pipe(cs=3, xs=3) == 1 and pipe(fst=[A, A + 8]) == 1
     assert pipe(order=2) == 1 and pipe(order=-1) == 1
     assert pipe(ev=[A] * 10 + [None]) == 1
+    # in place (no frame staging): misaligned blob, missing compute stream, short blob
+    assert pipe(fst=[], mst=[], chunks=[(A + 4, blob, 2048)]) == 1
+    assert pipe(fst=[], mst=[], xs=0) == 1
+    assert pipe(fst=[], mst=[], chunks=[(A, blob - 1, 2048)]) == 3
     # meta staging: a chunk section, or the pairs of three layers (K per channel, V per token and head)
     assert kvc.meta_staging_size(lo, kvc.KVC_ORDER_CHUNK) == mb
     slice_bytes = 3 * (8 * 128 + 2048 * 8) * 8
