@@ -249,6 +249,8 @@ kvc_status kvc_fetch_pipeline(const kvc_layout* layout, const kvc_host_chunk* ch
  *                as they sit in the chunk section from byte
  *                first_frame * kvc_frame_size(layout) on; 8-byte aligned
  *   meta         DEVICE in : the meta section of the chunk the frames belong to
+ *                (either may be pinned host memory mapped into the device, as
+ *                for kvc_restore_paged)
  *   first_frame, n_frames : 0 <= first_frame, n_frames >= 1,
  *                first_frame + n_frames <= 2*LG*F
  *   first_token  absolute position of the chunk's token 0 (multiple of T)
