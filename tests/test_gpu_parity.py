@@ -177,6 +177,20 @@ def test_frame_calls_and_in_place_pipelines_on_host_blobs(shape, dtype):
     kvc.kvc_fetch_pipeline(glo, chunks, [], 0, cache.ptrs.data_ptr(), nb, bs, tab.data_ptr(), tab.numel(),
                            cache.err.data_ptr(), 0, s_comp.cuda_stream, timed=True)
     check(cache, "chunk pipeline in place")
+    # untimed forms return after enqueueing; the caller synchronizes the compute stream
+    cache = hz.PagedCache(L, nb, bs, C)
+    torch.cuda.synchronize()
+    assert kvc.kvc_fetch_pipeline(glo, chunks, [], 0, cache.ptrs.data_ptr(), nb, bs, tab.data_ptr(), tab.numel(),
+                                  cache.err.data_ptr(), 0, s_comp.cuda_stream, timed=False) is None
+    s_comp.synchronize()
+    check(cache, "chunk pipeline in place, untimed")
+    cache = hz.PagedCache(L, nb, bs, C)
+    torch.cuda.synchronize()
+    assert kvc.kvc_fetch_pipeline_frames(glo, chunks, [], 0, [], 0, cache.ptrs.data_ptr(), nb, bs, tab.data_ptr(),
+                                         tab.numel(), cache.err.data_ptr(), 0, s_comp.cuda_stream,
+                                         order=kvc.KVC_ORDER_LAYER, timed=False) is None
+    s_comp.synchronize()
+    check(cache, "frame pipeline in place, layer order, untimed")
     for order in (kvc.KVC_ORDER_CHUNK, kvc.KVC_ORDER_LAYER):
         cache = hz.PagedCache(L, nb, bs, C)
         torch.cuda.synchronize()
