@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # this command, not in this one, and are keyed by the identifier the library carries (a hash of its sources,
 # header and compiler flags): for any other build the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "4d3e544bfd9671fa": {"pack": 6581945030, "restore": 6513935872},
+    "7dbfcbf189313beb": {"pack": 6582075512, "restore": 6513935843},
 }
 TRAFFIC_PROFILE = "profiles/pack_restore_llama3_8b_32k_paged.txt"
 

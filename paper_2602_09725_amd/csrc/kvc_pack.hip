@@ -344,6 +344,57 @@ __device__ __forceinline__ void pack_token_body(const PackParams& p, uint32_t un
 
 constexpr int kMaxStripAtoms = 16;  // 128 channels
 
+// The workgroup's column statistics (each thread: its 8 channels over the token rows it took) -> the strip's group
+// parameters: lanes of a wave that hold the same atom differ by multiples of strip_atoms and are merged first, one
+// lane per atom leaves the wave's extremes in LDS, one thread per channel finishes the reduction, derives the
+// parameters, writes the channel's {scale, mn} pair, and hands {mn, inv} to all threads through LDS.  Two barriers;
+// every thread of the workgroup must come here.
+template <int DT>
+__device__ __forceinline__ void strip_parameters(const PackParams& p, ColumnStats<DT>& st, uint32_t strip, uint32_t kind,
+                                                 uint32_t l, uint32_t c, float (*red_lo)[kMaxStripAtoms * 8],
+                                                 float (*red_hi)[kMaxStripAtoms * 8], float (&mnv)[8], float (&inv)[8]) {
+  const Geo& g = p.g;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t sa = (uint32_t)p.strip_atoms;
+  const uint32_t a = tid & (sa - 1u);
+  for (uint32_t m = sa; m < 64u; m <<= 1) st.merge_xor((int)m);
+  float lo[8], hi[8];
+  st.get(lo, hi);
+  const uint32_t wave = tid >> 6, lane = tid & 63u;
+  const uint32_t n_waves = blockDim.x >> 6;
+  if (lane < sa) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      red_lo[wave][lane * 8 + i] = lo[i];
+      red_hi[wave][lane * 8 + i] = hi[i];
+    }
+  }
+  __syncthreads();
+  float* par_mn = &red_lo[n_waves][0];
+  float* par_inv = &red_hi[n_waves][0];
+  if (tid < sa * 8u) {
+    float l0 = red_lo[0][tid], h0 = red_hi[0][tid];
+    for (uint32_t w = 1; w < n_waves; ++w) {
+      l0 = __builtin_fminf(l0, red_lo[w][tid]);
+      h0 = __builtin_fmaxf(h0, red_hi[w][tid]);
+    }
+    const GroupParams q = group_params(l0, h0);
+    par_mn[tid] = q.mn;
+    par_inv[tid] = q.inv;
+    const uint32_t ch = strip * sa * 8u + tid;
+    if (ch < (uint32_t)g.C) {
+      float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + ch);
+      *reinterpret_cast<f32x2*>(mp) = f32x2{q.scale, q.mn};
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    mnv[i] = par_mn[a * 8 + i];
+    inv[i] = par_inv[a * 8 + i];
+  }
+}
+
 // Streaming variant for chunks too long for the register-resident strip: the strip is read twice, once for the
 // column statistics and once to quantize -- except its last (kStreamTailLoads + kStreamStashLoads) * rows tokens
 // (3072 with 1024 threads), which wait on chip between the two passes: 16 loads per thread in registers, 8 more in the
@@ -435,44 +486,7 @@ __device__ __forceinline__ void pack_channel_body(const PackParams& p, uint32_t 
     }
 #pragma unroll
     for (int i = 0; i < NT; ++i) st.add(tail[i]);
-    // lanes holding the same atom differ by multiples of sa
-    for (uint32_t m = sa; m < 64u; m <<= 1) st.merge_xor((int)m);
-    float lo[8], hi[8];
-    st.get(lo, hi);
-    const uint32_t wave = tid >> 6, lane = tid & 63u;
-    const uint32_t n_waves = blockDim.x >> 6;
-    if (lane < sa) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        red_lo[wave][lane * 8 + i] = lo[i];
-        red_hi[wave][lane * 8 + i] = hi[i];
-      }
-    }
-    __syncthreads();
-    // one thread per channel of the strip finishes the reduction and derives the group's parameters
-    float* par_mn = &red_lo[n_waves][0];
-    float* par_inv = &red_hi[n_waves][0];
-    if (tid < sa * 8u) {
-      float l0 = red_lo[0][tid], h0 = red_hi[0][tid];
-      for (uint32_t w = 1; w < n_waves; ++w) {
-        l0 = __builtin_fminf(l0, red_lo[w][tid]);
-        h0 = __builtin_fmaxf(h0, red_hi[w][tid]);
-      }
-      const GroupParams q = group_params(l0, h0);
-      par_mn[tid] = q.mn;
-      par_inv[tid] = q.inv;
-      const uint32_t ch = strip * sa * 8u + tid;
-      if (ch < (uint32_t)g.C) {
-        float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + ch);
-        *reinterpret_cast<f32x2*>(mp) = f32x2{q.scale, q.mn};
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      mnv[i] = par_mn[a * 8 + i];
-      inv[i] = par_inv[a * 8 + i];
-    }
+    strip_parameters<DT>(p, st, strip, kind, l, c, red_lo, red_hi, mnv, inv);
   }
   if (!active) return;  // after the barriers: lanes of a ragged last strip store nothing
 
@@ -598,43 +612,7 @@ __device__ __forceinline__ void pack_channel_body_resident(const PackParams& p, 
     }
 #pragma unroll
     for (int i = 0; i < NR; ++i) st.add(v[i]);
-    for (uint32_t m = sa; m < 64u; m <<= 1) st.merge_xor((int)m);
-    float lo[8], hi[8];
-    st.get(lo, hi);
-    const uint32_t wave = tid >> 6, lane = tid & 63u;
-    const uint32_t n_waves = blockDim.x >> 6;
-    if (lane < sa) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        red_lo[wave][lane * 8 + i] = lo[i];
-        red_hi[wave][lane * 8 + i] = hi[i];
-      }
-    }
-    __syncthreads();
-    // one thread per channel of the strip finishes the reduction and derives the group's parameters
-    float* par_mn = &red_lo[n_waves][0];
-    float* par_inv = &red_hi[n_waves][0];
-    if (tid < sa * 8u) {
-      float l0 = red_lo[0][tid], h0 = red_hi[0][tid];
-      for (uint32_t w = 1; w < n_waves; ++w) {
-        l0 = __builtin_fminf(l0, red_lo[w][tid]);
-        h0 = __builtin_fmaxf(h0, red_hi[w][tid]);
-      }
-      const GroupParams q = group_params(l0, h0);
-      par_mn[tid] = q.mn;
-      par_inv[tid] = q.inv;
-      const uint32_t ch = strip * sa * 8u + tid;
-      if (ch < (uint32_t)g.C) {
-        float* mp = p.meta + (int64_t)c * g.meta_floats + g.meta_off[kind] + 2 * ((int64_t)l * g.C + ch);
-        *reinterpret_cast<f32x2*>(mp) = f32x2{q.scale, q.mn};
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      mnv[i] = par_mn[a * 8 + i];
-      inv[i] = par_inv[a * 8 + i];
-    }
+    strip_parameters<DT>(p, st, strip, kind, l, c, red_lo, red_hi, mnv, inv);
   }
   if (!active) return;  // after the barriers: lanes of a ragged last strip store nothing
 
